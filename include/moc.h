@@ -1,0 +1,152 @@
+/*
+ * moc.h - C ABI of the Mixture-of-Contexts (MoC) sparse attention layer for
+ * AMD MI355X (gfx950 / CDNA4).
+ *
+ * The layer (paper Sec. 3) has four stages, one entry point each:
+ *   (a) moc_chunk_meta  content-aligned chunk tables            (Sec. 3.2, 3.3)
+ *   (b,c) moc_route     mean-pooled chunk keys, query-chunk scores, per-query
+ *                       top-k with forced links and the causal routing mask
+ *                                                           (Eq. 3; Sec. 3.2, 3.3)
+ *   (d) moc_attn_fwd    softmax attention over the tokens of the forced and the
+ *                       routed chunks only                         (Eq. 2)
+ *       moc_attn_bwd    its backward, the selection being a constant (Sec. 3.1)
+ *
+ * Conventions
+ *   - All tensors are contiguous, head-major [B, H, N, d] (Sec. 3.3 "head-major
+ *     order"); B samples share ONE layout; K/V heads = Q heads.
+ *   - "HOST" pointers are read before the call returns. "DEVICE" pointers are
+ *     hipMalloc'ed memory owned by the caller; they must be 16-byte aligned.
+ *   - Every call only enqueues work on `stream` (a hipStream_t, may be NULL for
+ *     the default stream) and returns without synchronising, except
+ *     moc_chunk_meta / moc_meta_copy_tables which also do small blocking copies.
+ *   - The library allocates device memory only inside moc_chunk_meta (a few
+ *     small tables owned by the moc_meta handle). All other scratch space is a
+ *     caller-owned workspace whose size the *_workspace_bytes calls report.
+ *   - Return value: MOC_OK (0) or a negative moc_status. Nothing throws, aborts
+ *     or prints. All argument checks happen before any device work.
+ *     moc_last_error() returns a thread-local detail string of the last failure.
+ *   - d must be 64 or 128; 0 <= topk <= MOC_MAX_TOPK; N * max(topk,1) < 2^31.
+ */
+#ifndef MOC_H_
+#define MOC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOC_MAX_TOPK 32
+
+typedef enum moc_dtype {
+    MOC_BF16 = 0, /* bfloat16 storage for q/k/v/o/dO/dq/dk/dv */
+    MOC_F32 = 1   /* float32 storage; attention contractions still run on bf16
+                     matrix cores (operands rounded to nearest-even), routing
+                     scores are accumulated in fp32 from the fp32 values */
+} moc_dtype;
+
+typedef enum moc_status {
+    MOC_OK = 0,
+    MOC_ERR_NULL = -1,      /* a required pointer is NULL */
+    MOC_ERR_SHAPE = -2,     /* N, C, B, H <= 0; d not in {64,128}; topk out of range; N*topk overflow */
+    MOC_ERR_OFFSETS = -3,   /* chunk_offsets not strictly increasing from 0 to N */
+    MOC_ERR_TEXT_SPAN = -4, /* a text span is empty, out of range, overlapping, unsorted or not chunk-aligned */
+    MOC_ERR_WINDOW = -5,    /* equal window ids not contiguous, or a window spans two shots */
+    MOC_ERR_DTYPE = -6,     /* dtype is neither MOC_BF16 nor MOC_F32 */
+    MOC_ERR_WORKSPACE = -7, /* workspace NULL or smaller than *_workspace_bytes reports */
+    MOC_ERR_ALIGN = -8,     /* a device pointer is not 16-byte aligned */
+    MOC_ERR_HIP = -9,       /* a HIP runtime call or kernel launch failed */
+    MOC_ERR_SHOT = -10      /* chunk_shot decreases */
+} moc_status;
+
+const char *moc_status_string(int status);
+const char *moc_last_error(void);
+
+/* Opaque handle: owns only small device tables derived from the layout
+ * (token->chunk map, chunk kind / window tables, forced-link key ranges,
+ * query-tile lists of the forced-link pass). Reusable across layers, heads and
+ * steps that share the layout. Not tied to a stream after creation returns. */
+typedef struct moc_meta moc_meta;
+
+/*
+ * Stage (a): chunk tables (Sec. 3.3: boundary tags -> bucketize + prefix-sum
+ * tables -> content-aligned variable-length chunks; Sec. 3.2 forced links).
+ *   N, C            tokens and chunks of the flattened stream
+ *   chunk_offsets   HOST [C+1], off[0] = 0 < off[1] < ... < off[C] = N
+ *   chunk_shot      HOST [C], non-decreasing shot id per chunk
+ *   chunk_window    HOST [C] or NULL. Chunks with equal id form one local
+ *                   window and are mandatory for each other's queries (forced
+ *                   intra-shot link). Equal ids must be contiguous and lie in one
+ *                   shot. NULL: every chunk is its own window.
+ *   text_spans,T    HOST [T][2] token ranges [start,end) of caption spans,
+ *                   sorted, disjoint, each a union of whole chunks. Every query
+ *                   attends all of them (forced cross-modal link). T may be 0.
+ *   out             receives the handle; free with moc_meta_destroy.
+ */
+int moc_chunk_meta(int32_t N, int32_t C, const int32_t *chunk_offsets, const int32_t *chunk_shot,
+                   const int32_t *chunk_window, const int32_t *text_spans, int32_t T,
+                   void *stream, moc_meta **out);
+int moc_meta_destroy(moc_meta *meta);
+
+/* Test hook for stage (a): blocking copy of the device tables to HOST arrays
+ * (any may be NULL): chunk_of [N], chunk_kind [C] (1 = text, 0 = video),
+ * chunk_window [C] (dense ids in order of first appearance). */
+int moc_meta_copy_tables(const moc_meta *meta, int32_t *chunk_of, int32_t *chunk_kind,
+                         int32_t *chunk_window);
+
+/*
+ * Stages (b)+(c): routing.
+ *   pooled_k  DEVICE out [B,H,C,d] fp32: arithmetic mean of each chunk's keys
+ *             (the descriptor phi of Eq. 3), text chunks included.
+ *   sel       DEVICE out [B,H,N,topk] int32: for every query the routed chunks,
+ *             best score first, ties to the lower chunk index, -1 padded when
+ *             fewer than topk candidates exist. Candidates of query i in chunk
+ *             c(i): chunks that are neither text nor in c(i)'s window, and, when
+ *             causal != 0, have index < c(i). Score = q . pooled_k (no 1/sqrt d).
+ *   q, k      DEVICE in [B,H,N,d] of `dtype`.
+ *   workspace DEVICE scratch of moc_route_workspace_bytes bytes.
+ */
+int moc_route_workspace_bytes(const moc_meta *meta, int32_t B, int32_t H, int32_t d,
+                              int32_t topk, int dtype, size_t *bytes);
+int moc_route(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
+              const void *q, const void *k, int32_t topk, int32_t causal,
+              float *pooled_k, int32_t *sel, void *workspace, size_t workspace_bytes,
+              void *stream);
+
+/*
+ * Stage (d) forward: o_i = softmax(q_i K_Omega^T * softmax_scale) V_Omega with
+ * Omega(i) = tokens of all text chunks + the chunks of i's window + the chunks
+ * listed in sel[i] (entries < 0 ignored). Forced links are not subject to the
+ * causal mask. lse_i = log sum_t exp(logit_it) (natural log).
+ *   sel       DEVICE in [B,H,N,topk]; may come from moc_route or from anywhere
+ *             else; entries must be -1 or a video chunk outside i's window,
+ *             without repeats in a row.
+ *   o         DEVICE out [B,H,N,d] dtype;  lse DEVICE out [B,H,N] fp32.
+ *   workspace DEVICE scratch of moc_attn_workspace_bytes(..., with_bwd) bytes.
+ */
+int moc_attn_workspace_bytes(const moc_meta *meta, int32_t B, int32_t H, int32_t d,
+                             int32_t topk, int dtype, int with_bwd, size_t *bytes);
+int moc_attn_fwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
+                 const void *q, const void *k, const void *v, const int32_t *sel,
+                 int32_t topk, float softmax_scale, void *o, float *lse,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Stage (d) backward with Omega fixed (no gradient through scores or top-k):
+ *   delta_i = dO_i . o_i,  P_it = exp(logit_it - lse_i),
+ *   dV_t = sum_i P_it dO_i,  dS_it = P_it (dO_i . v_t - delta_i),
+ *   dQ_i = scale * sum_t dS_it k_t,  dK_t = scale * sum_i dS_it q_i.
+ * o, lse are the forward's outputs; dq, dk, dv [B,H,N,d] dtype are fully
+ * overwritten. workspace must have been sized with with_bwd = 1.
+ */
+int moc_attn_bwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
+                 const void *q, const void *k, const void *v, const void *o, const float *lse,
+                 const void *d_o, const int32_t *sel, int32_t topk, float softmax_scale,
+                 void *dq, void *dk, void *dv, void *workspace, size_t workspace_bytes,
+                 void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOC_H_ */

@@ -1,0 +1,203 @@
+"""Thin ctypes binding of libmoc.so: argument marshalling only.
+
+Every step of the layer runs inside the HIP library; torch is used for device
+memory and for the current stream. The functions mirror the C entry points of
+include/moc.h (moc_chunk_meta, moc_route, moc_attn_fwd, moc_attn_bwd).
+There is no fallback: if the library is missing and cannot be built, loading
+raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIBPATH = os.path.join(_HERE, "libmoc.so")
+_lib = None
+
+MOC_BF16, MOC_F32 = 0, 1
+MOC_MAX_TOPK = 32
+
+SYMBOLS = ["moc_status_string", "moc_last_error", "moc_chunk_meta", "moc_meta_destroy", "moc_meta_copy_tables",
+           "moc_route_workspace_bytes", "moc_route", "moc_attn_workspace_bytes", "moc_attn_fwd", "moc_attn_bwd"]
+
+
+class MocError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        l = lib()
+        self.status = status
+        msg = l.moc_status_string(status).decode()
+        detail = l.moc_last_error().decode()
+        super().__init__(f"{where}: {msg} ({status}): {detail}")
+
+
+def lib():
+    """Load libmoc.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIBPATH):
+        from . import build as _build
+        _build.build()
+    l = C.CDLL(_LIBPATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    l.moc_status_string.restype = C.c_char_p
+    l.moc_status_string.argtypes = [C.c_int]
+    l.moc_last_error.restype = C.c_char_p
+    l.moc_last_error.argtypes = []
+    l.moc_chunk_meta.argtypes = [i32, i32, vp, vp, vp, vp, i32, vp, C.POINTER(vp)]
+    l.moc_meta_destroy.argtypes = [vp]
+    l.moc_meta_copy_tables.argtypes = [vp, vp, vp, vp]
+    l.moc_route_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.c_int, C.POINTER(sz)]
+    l.moc_route.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    l.moc_attn_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.c_int, C.c_int, C.POINTER(sz)]
+    l.moc_attn_fwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, sz, vp]
+    l.moc_attn_bwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, i32, C.c_float,
+                               vp, vp, vp, vp, sz, vp]
+    for name in SYMBOLS:
+        if name not in ("moc_status_string", "moc_last_error"):
+            getattr(l, name).restype = C.c_int
+    _lib = l
+    return l
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise MocError(rc, where)
+
+
+def _stream():
+    """Current torch stream handle; None (the default stream) when no GPU is
+    present, so that argument validation can be exercised on a CPU-only host."""
+    if not torch.cuda.is_available():
+        return None
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return MOC_BF16
+    if t.dtype == torch.float32:
+        return MOC_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+class Meta:
+    """Owner of a moc_meta handle (stage a)."""
+
+    def __init__(self, handle, N, C_, T):
+        self.handle, self.N, self.C, self.T = handle, N, C_, T
+
+    def tables(self):
+        """Device tables copied back: (chunk_of [N], chunk_kind [C], chunk_window [C])."""
+        cof = np.zeros(self.N, np.int32)
+        kind = np.zeros(self.C, np.int32)
+        win = np.zeros(self.C, np.int32)
+        _check(lib().moc_meta_copy_tables(self.handle, cof.ctypes.data, kind.ctypes.data, win.ctypes.data),
+               "moc_meta_copy_tables")
+        return cof, kind, win
+
+    def close(self):
+        if self.handle:
+            lib().moc_meta_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def chunk_meta(offsets, shot, window=None, text_spans=None) -> Meta:
+    off, sh = _i32(offsets), _i32(shot)
+    win = None if window is None else _i32(window)
+    spans = _i32(text_spans).reshape(-1, 2) if text_spans is not None else np.zeros((0, 2), np.int32)
+    Cn, N, T = off.shape[0] - 1, int(off[-1]) if off.size else 0, spans.shape[0]
+    h = C.c_void_p()
+    rc = lib().moc_chunk_meta(N, Cn, off.ctypes.data, sh.ctypes.data, None if win is None else win.ctypes.data,
+                              spans.ctypes.data if T else None, T, _stream(), C.byref(h))
+    _check(rc, "moc_chunk_meta")
+    return Meta(h, N, Cn, T)
+
+
+def _shape(meta: Meta, q: torch.Tensor):
+    B, H, N, d = q.shape
+    if N != meta.N:
+        raise ValueError(f"tensor has N={N}, layout has N={meta.N}")
+    return B, H, N, d
+
+
+def _need_contig(*ts):
+    for t in ts:
+        if t is not None and not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("tensors must be contiguous CUDA tensors")
+
+
+def route(meta: Meta, q: torch.Tensor, k: torch.Tensor, topk: int, causal: bool = True
+          ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """-> pooled_k [B,H,C,d] fp32, sel [B,H,N,topk] int32."""
+    B, H, N, d = _shape(meta, q)
+    _need_contig(q, k)
+    dt = _dtype_code(q)
+    nbytes = C.c_size_t()
+    _check(lib().moc_route_workspace_bytes(meta.handle, B, H, d, topk, dt, C.byref(nbytes)),
+           "moc_route_workspace_bytes")
+    ws = torch.empty(max(nbytes.value, 16), dtype=torch.uint8, device=q.device)
+    pooled = torch.empty(B, H, meta.C, d, dtype=torch.float32, device=q.device)
+    sel = torch.empty(B, H, N, max(topk, 0), dtype=torch.int32, device=q.device)
+    _check(lib().moc_route(meta.handle, B, H, d, dt, _ptr(q), _ptr(k), topk, int(bool(causal)), _ptr(pooled),
+                           _ptr(sel) if topk > 0 else None, _ptr(ws), nbytes.value, _stream()), "moc_route")
+    return pooled, sel
+
+
+def attn_workspace(meta: Meta, B: int, H: int, d: int, topk: int, dtype: torch.dtype, with_bwd: bool,
+                   device="cuda") -> torch.Tensor:
+    dt = MOC_BF16 if dtype == torch.bfloat16 else MOC_F32
+    nbytes = C.c_size_t()
+    _check(lib().moc_attn_workspace_bytes(meta.handle, B, H, d, topk, dt, int(with_bwd), C.byref(nbytes)),
+           "moc_attn_workspace_bytes")
+    return torch.empty(max(nbytes.value, 16), dtype=torch.uint8, device=device)
+
+
+def attn_fwd(meta: Meta, q, k, v, sel, scale: Optional[float] = None, workspace: Optional[torch.Tensor] = None,
+             out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None):
+    """-> o [B,H,N,d] (dtype of q), lse [B,H,N] fp32."""
+    B, H, N, d = _shape(meta, q)
+    _need_contig(q, k, v, sel)
+    topk = int(sel.shape[-1])
+    scale = float(d ** -0.5 if scale is None else scale)
+    ws = workspace if workspace is not None else attn_workspace(meta, B, H, d, topk, q.dtype, False, q.device)
+    o, lse = out if out is not None else (torch.empty_like(q),
+                                          torch.empty(B, H, N, dtype=torch.float32, device=q.device))
+    _check(lib().moc_attn_fwd(meta.handle, B, H, d, _dtype_code(q), _ptr(q), _ptr(k), _ptr(v),
+                              _ptr(sel) if topk > 0 else None, topk, scale, _ptr(o), _ptr(lse), _ptr(ws),
+                              ws.numel(), _stream()), "moc_attn_fwd")
+    return o, lse
+
+
+def attn_bwd(meta: Meta, q, k, v, o, lse, d_o, sel, scale: Optional[float] = None,
+             workspace: Optional[torch.Tensor] = None, out=None):
+    """-> dq, dk, dv [B,H,N,d] (dtype of q)."""
+    B, H, N, d = _shape(meta, q)
+    _need_contig(q, k, v, o, lse, d_o, sel)
+    topk = int(sel.shape[-1])
+    scale = float(d ** -0.5 if scale is None else scale)
+    ws = workspace if workspace is not None else attn_workspace(meta, B, H, d, topk, q.dtype, True, q.device)
+    dq, dk, dv = out if out is not None else (torch.empty_like(q), torch.empty_like(q), torch.empty_like(q))
+    _check(lib().moc_attn_bwd(meta.handle, B, H, d, _dtype_code(q), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+                              _ptr(d_o), _ptr(sel) if topk > 0 else None, topk, scale, _ptr(dq), _ptr(dk), _ptr(dv),
+                              _ptr(ws), ws.numel(), _stream()), "moc_attn_bwd")
+    return dq, dk, dv

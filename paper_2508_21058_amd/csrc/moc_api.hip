@@ -1,0 +1,353 @@
+// C ABI of libmoc: argument validation, layout tables (stage a), workspace
+// layout, and dispatch to the kernel launchers. No kernel code in this file.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <unordered_set>
+#include <vector>
+
+#include "moc_internal.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string &detail) {
+    g_err = detail;
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what) {
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    return MOC_ERR_HIP;
+}
+
+size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_common(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int32_t topk, int dtype) {
+    if (!meta) return fail(MOC_ERR_NULL, "meta is NULL");
+    if (dtype != MOC_BF16 && dtype != MOC_F32) return fail(MOC_ERR_DTYPE, "dtype must be MOC_BF16 or MOC_F32");
+    if (B <= 0 || H <= 0) return fail(MOC_ERR_SHAPE, "B and H must be positive");
+    if (d != 64 && d != 128) return fail(MOC_ERR_SHAPE, "d must be 64 or 128");
+    if (topk < 0 || topk > MOC_MAX_TOPK) return fail(MOC_ERR_SHAPE, "topk out of range [0, MOC_MAX_TOPK]");
+    if ((long long)meta->N * std::max(topk, 1) >= (1LL << 31)) return fail(MOC_ERR_SHAPE, "N * topk must be < 2^31");
+    if ((long long)B * H > 65535) return fail(MOC_ERR_SHAPE, "B * H must be <= 65535");
+    return MOC_OK;
+}
+
+}  // namespace
+
+namespace moc {
+
+AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd) {
+    AttnWs L{};
+    size_t off = 0;
+    const size_t C = m->C, N = m->N, slots = (size_t)topk + 1;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    L.cnt = take((size_t)BH * C * 4);
+    L.list_off = take((size_t)BH * (C + 1) * 4);
+    L.tile_off = take((size_t)BH * (C + 1) * 4);
+    L.cursor = take((size_t)BH * C * 4);
+    L.qlist = take((size_t)BH * N * std::max(topk, 1) * 4);
+    L.plse = take((size_t)BH * N * slots * 4);
+    L.po = take((size_t)BH * N * slots * d * 2);
+    if (with_bwd) {
+        L.delta = take((size_t)BH * N * 4);
+        L.tpart_k = take((size_t)BH * m->n_partials * kKeyTile * d * 4);
+        L.tpart_v = take((size_t)BH * m->n_partials * kKeyTile * d * 4);
+    }
+    L.total = off;
+    return L;
+}
+
+RouteWs route_ws_layout(const moc_meta *, int, int, int, int) { return RouteWs{256}; }
+
+}  // namespace moc
+
+extern "C" {
+
+const char *moc_status_string(int s) {
+    switch (s) {
+        case MOC_OK: return "ok";
+        case MOC_ERR_NULL: return "null pointer";
+        case MOC_ERR_SHAPE: return "bad shape";
+        case MOC_ERR_OFFSETS: return "bad chunk offsets";
+        case MOC_ERR_TEXT_SPAN: return "bad text span";
+        case MOC_ERR_WINDOW: return "bad window ids";
+        case MOC_ERR_DTYPE: return "bad dtype";
+        case MOC_ERR_WORKSPACE: return "workspace missing or too small";
+        case MOC_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case MOC_ERR_HIP: return "HIP error";
+        case MOC_ERR_SHOT: return "shot ids decrease";
+        default: return "unknown status";
+    }
+}
+
+const char *moc_last_error(void) { return g_err.c_str(); }
+
+int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot, const int32_t *window,
+                   const int32_t *spans, int32_t T, void *stream, moc_meta **out) {
+    using namespace moc;
+    if (!out) return fail(MOC_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    if (!off || !shot) return fail(MOC_ERR_NULL, "chunk_offsets / chunk_shot is NULL");
+    if (T < 0 || (T > 0 && !spans)) return fail(MOC_ERR_NULL, "text_spans is NULL with T > 0");
+    if (N <= 0 || C <= 0 || C > N) return fail(MOC_ERR_SHAPE, "need 0 < C <= N");
+    if (off[0] != 0 || off[C] != N) return fail(MOC_ERR_OFFSETS, "offsets must start at 0 and end at N");
+    for (int j = 0; j < C; ++j)
+        if (off[j + 1] <= off[j]) return fail(MOC_ERR_OFFSETS, "offsets must be strictly increasing");
+    for (int j = 1; j < C; ++j)
+        if (shot[j] < shot[j - 1]) return fail(MOC_ERR_SHOT, "chunk_shot must be non-decreasing");
+
+    // text spans: sorted, disjoint, non-empty, chunk-aligned
+    std::vector<int32_t> kind(C, 0);
+    {
+        int prev_end = 0;
+        for (int s = 0; s < T; ++s) {
+            int a = spans[2 * s], b = spans[2 * s + 1];
+            if (a < 0 || b > N || a >= b) return fail(MOC_ERR_TEXT_SPAN, "text span empty or out of range");
+            if (a < prev_end) return fail(MOC_ERR_TEXT_SPAN, "text spans must be sorted and disjoint");
+            prev_end = b;
+            const int32_t *pa = std::lower_bound(off, off + C + 1, a);
+            const int32_t *pb = std::lower_bound(off, off + C + 1, b);
+            if (*pa != a || *pb != b) return fail(MOC_ERR_TEXT_SPAN, "text span is not a union of whole chunks");
+            for (int j = int(pa - off); j < int(pb - off); ++j) kind[j] = 1;
+        }
+    }
+
+    // dense window ids; equal ids must be contiguous and inside one shot
+    std::vector<int32_t> win(C), wfirst, wlast;
+    {
+        std::unordered_set<int32_t> seen;
+        for (int j = 0; j < C; ++j) {
+            bool fresh = (j == 0) || !window || window[j] != window[j - 1];
+            if (fresh) {
+                if (window && !seen.insert(window[j]).second)
+                    return fail(MOC_ERR_WINDOW, "equal window ids must be contiguous");
+                wfirst.push_back(j);
+                wlast.push_back(j);
+            } else {
+                if (shot[j] != shot[wfirst.back()]) return fail(MOC_ERR_WINDOW, "a window spans two shots");
+                wlast.back() = j;
+            }
+            win[j] = int32_t(wfirst.size()) - 1;
+        }
+    }
+    const int W = int(wfirst.size());
+
+    // forced-link key ranges per window: union of all text spans and the window's own tokens
+    std::vector<int32_t> arange_off(W + 1, 0);
+    std::vector<KeyRange> aranges;
+    std::vector<AnchorTile> atiles;
+    for (int w = 0; w < W; ++w) {
+        std::vector<std::pair<int, int>> iv;
+        for (int s = 0; s < T; ++s) iv.emplace_back(spans[2 * s], spans[2 * s + 1]);
+        const int ws = off[wfirst[w]], we = off[wlast[w] + 1];
+        iv.emplace_back(ws, we);
+        std::sort(iv.begin(), iv.end());
+        std::vector<std::pair<int, int>> merged;
+        for (auto &p : iv) {
+            if (!merged.empty() && p.first <= merged.back().second)
+                merged.back().second = std::max(merged.back().second, p.second);
+            else
+                merged.push_back(p);
+        }
+        for (auto &p : merged) aranges.push_back(KeyRange{p.first, p.second - p.first});
+        arange_off[w + 1] = int32_t(aranges.size());
+        for (int q0 = ws; q0 < we; q0 += kBM) atiles.push_back(AnchorTile{q0, std::min(kBM, we - q0), w, 0});
+    }
+
+    // key-stationary backward items
+    std::vector<KvItem> kvitems;
+    std::vector<TextTile> ttiles;
+    int n_partials = 0;
+    for (int j = 0; j < C; ++j) {
+        for (int k0 = off[j]; k0 < off[j + 1]; k0 += kKeyTile) {
+            const int klen = std::min(kKeyTile, off[j + 1] - k0);
+            if (kind[j]) {
+                const int nseg = (N + kTextSeg - 1) / kTextSeg;
+                ttiles.push_back(TextTile{k0, klen, n_partials, nseg});
+                for (int s = 0; s < nseg; ++s)
+                    kvitems.push_back(KvItem{k0, klen, s * kTextSeg, std::min(kTextSeg, N - s * kTextSeg), -1,
+                                             n_partials + s, 0, 0});
+                n_partials += nseg;
+            } else {
+                const int w = win[j];
+                const int ws = off[wfirst[w]], we = off[wlast[w] + 1];
+                kvitems.push_back(KvItem{k0, klen, ws, we - ws, j, -1, 0, 0});
+            }
+        }
+    }
+
+    moc_meta *m = new (std::nothrow) moc_meta();
+    if (!m) return fail(MOC_ERR_HIP, "host allocation failed");
+    m->N = N; m->C = C; m->T = T; m->W = W;
+    m->n_atiles = int32_t(atiles.size());
+    m->n_ranges = int32_t(aranges.size());
+    m->n_kvitems = int32_t(kvitems.size());
+    m->n_text_tiles = int32_t(ttiles.size());
+    m->n_partials = n_partials;
+    m->h_off.assign(off, off + C + 1);
+    m->h_kind = kind;
+    m->h_win = win;
+
+    // one device allocation, one blocking upload
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + std::max<size_t>(bytes, 16)); return r; };
+    const size_t o_off = take((size_t)(C + 1) * 4), o_kind = take((size_t)C * 4), o_win = take((size_t)C * 4),
+                 o_wf = take((size_t)W * 4), o_wl = take((size_t)W * 4), o_aro = take((size_t)(W + 1) * 4),
+                 o_ar = take(aranges.size() * sizeof(KeyRange)), o_at = take(atiles.size() * sizeof(AnchorTile)),
+                 o_kv = take(kvitems.size() * sizeof(KvItem)), o_tt = take(ttiles.size() * sizeof(TextTile)),
+                 o_cof = take((size_t)N * 4);
+    const size_t upload = o_cof;  // chunk_of is filled on the device
+    std::vector<char> host(upload, 0);
+    auto put = [&](size_t at, const void *src, size_t bytes) { if (bytes) std::memcpy(host.data() + at, src, bytes); };
+    put(o_off, off, (size_t)(C + 1) * 4);
+    put(o_kind, kind.data(), (size_t)C * 4);
+    put(o_win, win.data(), (size_t)C * 4);
+    put(o_wf, wfirst.data(), (size_t)W * 4);
+    put(o_wl, wlast.data(), (size_t)W * 4);
+    put(o_aro, arange_off.data(), (size_t)(W + 1) * 4);
+    put(o_ar, aranges.data(), aranges.size() * sizeof(KeyRange));
+    put(o_at, atiles.data(), atiles.size() * sizeof(AnchorTile));
+    put(o_kv, kvitems.data(), kvitems.size() * sizeof(KvItem));
+    put(o_tt, ttiles.data(), ttiles.size() * sizeof(TextTile));
+
+    hipError_t e = hipMalloc(&m->d_base, o);
+    if (e != hipSuccess) { delete m; return hip_fail(e, "hipMalloc(meta tables)"); }
+    m->d_bytes = o;
+    char *base = static_cast<char *>(m->d_base);
+    m->d_off = reinterpret_cast<int32_t *>(base + o_off);
+    m->d_kind = reinterpret_cast<int32_t *>(base + o_kind);
+    m->d_win = reinterpret_cast<int32_t *>(base + o_win);
+    m->d_wfirst = reinterpret_cast<int32_t *>(base + o_wf);
+    m->d_wlast = reinterpret_cast<int32_t *>(base + o_wl);
+    m->d_arange_off = reinterpret_cast<int32_t *>(base + o_aro);
+    m->d_aranges = reinterpret_cast<KeyRange *>(base + o_ar);
+    m->d_atiles = reinterpret_cast<AnchorTile *>(base + o_at);
+    m->d_kvitems = reinterpret_cast<KvItem *>(base + o_kv);
+    m->d_text_tiles = reinterpret_cast<TextTile *>(base + o_tt);
+    m->d_chunk_of = reinterpret_cast<int32_t *>(base + o_cof);
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    e = hipMemcpy(m->d_base, host.data(), upload, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = launch_chunk_of(m, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) {
+        (void)hipFree(m->d_base);
+        delete m;
+        return hip_fail(e, "moc_chunk_meta upload");
+    }
+    *out = m;
+    return MOC_OK;
+}
+
+int moc_meta_destroy(moc_meta *m) {
+    if (!m) return MOC_OK;
+    hipError_t e = m->d_base ? hipFree(m->d_base) : hipSuccess;
+    delete m;
+    return e == hipSuccess ? MOC_OK : hip_fail(e, "hipFree(meta tables)");
+}
+
+int moc_meta_copy_tables(const moc_meta *m, int32_t *chunk_of, int32_t *kind, int32_t *win) {
+    if (!m) return fail(MOC_ERR_NULL, "meta is NULL");
+    hipError_t e = hipSuccess;
+    if (chunk_of) e = hipMemcpy(chunk_of, m->d_chunk_of, (size_t)m->N * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && kind) e = hipMemcpy(kind, m->d_kind, (size_t)m->C * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && win) e = hipMemcpy(win, m->d_win, (size_t)m->C * 4, hipMemcpyDeviceToHost);
+    return e == hipSuccess ? MOC_OK : hip_fail(e, "moc_meta_copy_tables");
+}
+
+int moc_route_workspace_bytes(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int32_t topk, int dtype,
+                              size_t *bytes) {
+    if (!bytes) return fail(MOC_ERR_NULL, "bytes is NULL");
+    int rc = check_common(meta, B, H, d, topk, dtype);
+    if (rc) return rc;
+    *bytes = moc::route_ws_layout(meta, B * H, d, topk, dtype).total;
+    return MOC_OK;
+}
+
+int moc_route(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
+              int32_t topk, int32_t causal, float *pooled_k, int32_t *sel, void *workspace, size_t workspace_bytes,
+              void *stream) {
+    int rc = check_common(meta, B, H, d, topk, dtype);
+    if (rc) return rc;
+    if (!q || !k || !pooled_k || (!sel && topk > 0)) return fail(MOC_ERR_NULL, "q, k, pooled_k or sel is NULL");
+    if (misaligned(q) || misaligned(k) || misaligned(pooled_k) || misaligned(sel))
+        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    const size_t need = moc::route_ws_layout(meta, B * H, d, topk, dtype).total;
+    if (!workspace || workspace_bytes < need) return fail(MOC_ERR_WORKSPACE, "route workspace too small");
+    if (misaligned(workspace)) return fail(MOC_ERR_ALIGN, "workspace must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = moc::launch_pool(meta, B * H, d, dtype, k, pooled_k, st);
+    if (e != hipSuccess) return hip_fail(e, "pool kernel");
+    if (topk > 0) {
+        e = moc::launch_route(meta, B * H, d, dtype, q, pooled_k, topk, causal, sel, st);
+        if (e != hipSuccess) return hip_fail(e, "route kernel");
+    }
+    return MOC_OK;
+}
+
+int moc_attn_workspace_bytes(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int32_t topk, int dtype,
+                             int with_bwd, size_t *bytes) {
+    if (!bytes) return fail(MOC_ERR_NULL, "bytes is NULL");
+    int rc = check_common(meta, B, H, d, topk, dtype);
+    if (rc) return rc;
+    *bytes = moc::attn_ws_layout(meta, B * H, d, topk, with_bwd != 0).total;
+    return MOC_OK;
+}
+
+int moc_attn_fwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
+                 const void *v, const int32_t *sel, int32_t topk, float softmax_scale, void *o, float *lse,
+                 void *workspace, size_t workspace_bytes, void *stream) {
+    int rc = check_common(meta, B, H, d, topk, dtype);
+    if (rc) return rc;
+    if (!q || !k || !v || !o || !lse || (!sel && topk > 0)) return fail(MOC_ERR_NULL, "a tensor pointer is NULL");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) || misaligned(sel))
+        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    const moc::AttnWs L = moc::attn_ws_layout(meta, B * H, d, topk, false);
+    if (!workspace || workspace_bytes < L.total) return fail(MOC_ERR_WORKSPACE, "attention workspace too small");
+    if (misaligned(workspace)) return fail(MOC_ERR_ALIGN, "workspace must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    if (topk > 0) {
+        e = moc::launch_build_lists(meta, B * H, topk, sel, static_cast<char *>(workspace), L, st);
+        if (e != hipSuccess) return hip_fail(e, "list kernels");
+    }
+    e = moc::launch_attn_fwd(meta, B * H, d, dtype, q, k, v, sel, topk, softmax_scale, o, lse,
+                             static_cast<char *>(workspace), L, st);
+    if (e != hipSuccess) return hip_fail(e, "attention forward kernels");
+    return MOC_OK;
+}
+
+int moc_attn_bwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
+                 const void *v, const void *o, const float *lse, const void *d_o, const int32_t *sel, int32_t topk,
+                 float softmax_scale, void *dq, void *dk, void *dv, void *workspace, size_t workspace_bytes,
+                 void *stream) {
+    int rc = check_common(meta, B, H, d, topk, dtype);
+    if (rc) return rc;
+    if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || (!sel && topk > 0))
+        return fail(MOC_ERR_NULL, "a tensor pointer is NULL");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) || misaligned(d_o) ||
+        misaligned(dq) || misaligned(dk) || misaligned(dv) || misaligned(sel))
+        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    const moc::AttnWs L = moc::attn_ws_layout(meta, B * H, d, topk, true);
+    if (!workspace || workspace_bytes < L.total) return fail(MOC_ERR_WORKSPACE, "attention workspace too small (with_bwd)");
+    if (misaligned(workspace)) return fail(MOC_ERR_ALIGN, "workspace must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    if (topk > 0) {
+        e = moc::launch_build_lists(meta, B * H, topk, sel, static_cast<char *>(workspace), L, st);
+        if (e != hipSuccess) return hip_fail(e, "list kernels");
+    }
+    e = moc::launch_attn_bwd(meta, B * H, d, dtype, q, k, v, o, lse, d_o, sel, topk, softmax_scale, dq, dk, dv,
+                             static_cast<char *>(workspace), L, st);
+    if (e != hipSuccess) return hip_fail(e, "attention backward kernels");
+    return MOC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,401 @@
+// Stage (d) backward with the routed set fixed (Sec. 3.1: top-k is not
+// differentiable; the gradient reaches q, k, v only through attention on the
+// selected tokens).
+//
+//   delta_i = dO_i . o_i
+//   P_it = exp(scale * q_i.k_t - lse_i),  dS_it = P_it (dO_i.v_t - delta_i)
+//   dV_t = sum_i P_it dO_i,  dK_t = scale sum_i dS_it q_i,  dQ_i = scale sum_t dS_it k_t
+//
+// Two passes over the same dense items as the forward, neither uses atomics:
+//   dQ pass    query-stationary (forced-link items and routed items, exactly the
+//              forward's work list); each item writes its partial dQ to the slot
+//              of its (query, link) pair, a merge kernel adds the slots.
+//   dK/dV pass key-stationary: a workgroup owns <= 128 keys of one chunk and
+//              walks every query that attends them - the chunk's window
+//              (contiguous) and the chunk's inverse routing list (gathered) -
+//              so dK and dV of video tokens are written once, final. Text keys
+//              are attended by all N queries; their items split the queries
+//              into segments, write fp32 partials, and a reduce kernel sums them.
+#include "moc_attn_common.h"
+
+namespace moc {
+
+// ------------------------------------------------------------------ delta
+template <int D, typename T>
+__global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ o, const T *__restrict__ d_o, size_t rows,
+                                                    float *__restrict__ delta) {
+    constexpr int TPQ = D / 8, QPW = 256 / TPQ;
+    const size_t row = (size_t)blockIdx.x * QPW + threadIdx.x / TPQ;
+    const int c8 = threadIdx.x % TPQ;
+    float s = 0.f;
+    if (row < rows) {
+        float a[8], b[8];
+        Io<T>::load8f(o + row * D + c8 * 8, a);
+        Io<T>::load8f(d_o + row * D + c8 * 8, b);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s = fmaf(a[e], b[e], s);
+    }
+#pragma unroll
+    for (int w = TPQ / 2; w >= 1; w >>= 1) s += __shfl_xor(s, w, 64);
+    if (row < rows && c8 == 0) delta[row] = s;
+}
+
+// ------------------------------------------------------------------ dQ pass
+template <int D, typename T, int MODE>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(FwdArgs a) {
+    constexpr int BN = 32;
+    constexpr int KS = D / 16, DB = D / 32;
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[BN * RowTile<D>::kStride];
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[BN * RowTile<D>::kStride];
+    __shared__ __attribute__((aligned(16))) bf16_t Kt[D * ColTile<BN>::kStride];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int bh = blockIdx.y;
+    const int N = a.N;
+
+    ItemDesc it;
+    if (!decode_item<MODE>(a, bh, blockIdx.x, it)) return;
+
+    const int r = wave * 32 + l32;
+    const bool row_valid = r < it.q_count;
+    const bool wave_active = wave * 32 < it.q_count;
+    const int rc = row_valid ? r : it.q_count - 1;
+    int qi, slot;
+    if (MODE == MODE_ANCHOR) { qi = it.q_start + rc; slot = a.topk; }
+    else { const int e = it.entries[rc]; qi = e / a.topk; slot = e - qi * a.topk; }
+
+    const T *qbase = static_cast<const T *>(a.q) + (size_t)bh * N * D;
+    const T *kbase = static_cast<const T *>(a.k) + (size_t)bh * N * D;
+    const T *vbase = static_cast<const T *>(a.v) + (size_t)bh * N * D;
+    const T *dobase = static_cast<const T *>(a.d_o) + (size_t)bh * N * D;
+
+    bf16x8 qf[KS], dof[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        qf[s] = Io<T>::load8(qbase + (size_t)qi * D + s * 16 + half * 8);
+        dof[s] = Io<T>::load8(dobase + (size_t)qi * D + s * 16 + half * 8);
+    }
+    const float c = a.scale_log2;
+    const float lse2 = a.lse[(size_t)bh * N + qi] * kLog2e;
+    const float dl = a.delta[(size_t)bh * N + qi];
+
+    f32x16 dqacc[DB];
+#pragma unroll
+    for (int b = 0; b < DB; ++b) dqacc[b] = zero16();
+
+    RowStager<D, T, BN> kst(tid), vst(tid);
+    ColStager<D, T, BN> ktst(tid);
+    TileIter<BN> ti(it);
+    kst.load(kbase, ti.start(), ti.valid());
+    vst.load(vbase, ti.start(), ti.valid());
+    ktst.load(kbase, ti.start(), ti.valid());
+    while (true) {
+        __syncthreads();
+        kst.store(Ks);
+        vst.store(Vs);
+        ktst.store(Kt);
+        __syncthreads();
+        const int valid = ti.valid();
+        const bool more = ti.next();
+        if (more) {
+            kst.load(kbase, ti.start(), ti.valid());
+            vst.load(vbase, ti.start(), ti.valid());
+            ktst.load(kbase, ti.start(), ti.valid());
+        }
+        if (wave_active) {
+            f32x16 sacc = zero16(), dpacc = zero16();
+#pragma unroll
+            for (int s = 0; s < KS; ++s) sacc = mfma32(RowTile<D>::frag(Ks, l32, s, half), qf[s], sacc);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) dpacc = mfma32(RowTile<D>::frag(Vs, l32, s, half), dof[s], dpacc);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int key = (i >> 2) * 8 + half * 4 + (i & 3);
+                float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, -lse2));
+                if (key >= valid) p = 0.f;
+                sacc[i] = p * (dpacc[i] - dl);
+            }
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                if (ks * 16 < valid) {
+                    const bf16x8 dsf = acc_to_frag(sacc, ks);
+#pragma unroll
+                    for (int b = 0; b < DB; ++b)
+                        dqacc[b] = mfma32(ColTile<BN>::frag(Kt, b * 32 + l32, ks, half), dsf, dqacc[b]);
+                }
+            }
+        }
+        if (!more) break;
+    }
+    if (!row_valid) return;
+    bf16_t *po = a.po + (((size_t)bh * N + qi) * a.slots + slot) * D;
+    const float sc = a.scale;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int x = b * 32 + g * 8 + half * 4;
+            Io<bf16_t>::store4(po + x, dqacc[b][4 * g] * sc, dqacc[b][4 * g + 1] * sc, dqacc[b][4 * g + 2] * sc,
+                               dqacc[b][4 * g + 3] * sc);
+        }
+}
+
+template <int D, typename T>
+__global__ __launch_bounds__(256) void dq_merge_kernel(const bf16_t *__restrict__ part,
+                                                       const int32_t *__restrict__ sel, int N, int C, int topk,
+                                                       T *__restrict__ dq) {
+    constexpr int TPQ = D / 8, QPW = 256 / TPQ;
+    const int bh = blockIdx.y;
+    const int i = blockIdx.x * QPW + threadIdx.x / TPQ;
+    const int c8 = threadIdx.x % TPQ;
+    if (i >= N) return;
+    const int slots = topk + 1;
+    const size_t row = (size_t)bh * N + i;
+    const int32_t *sr = sel + row * topk;
+    float acc[8], f[8];
+    Io<bf16_t>::load8f(part + (row * slots + topk) * D + c8 * 8, acc);
+    for (int s = 0; s < topk; ++s) {
+        const int j = sr[s];
+        if (j >= 0 && j < C) {
+            Io<bf16_t>::load8f(part + (row * slots + s) * D + c8 * 8, f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += f[e];
+        }
+    }
+    Io<T>::store8(dq + row * D + c8 * 8, acc);
+}
+
+// ------------------------------------------------------------------ dK/dV pass
+struct KvArgs {
+    const void *q, *k, *v, *d_o;
+    const float *lse, *delta;
+    void *dk, *dv;
+    float *tpart_k, *tpart_v;
+    const KvItem *items;
+    const int32_t *list_off, *qlist;
+    int N, C, topk, n_partials;
+    float scale, scale_log2;
+};
+
+template <int D, typename T>
+__global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
+    constexpr int BQ = 32;
+    constexpr int KS = D / 16, DB = D / 32;
+    __shared__ __attribute__((aligned(16))) bf16_t Qs[BQ * RowTile<D>::kStride];
+    __shared__ __attribute__((aligned(16))) bf16_t dOs[BQ * RowTile<D>::kStride];
+    __shared__ __attribute__((aligned(16))) bf16_t Qt[D * ColTile<BQ>::kStride];
+    __shared__ __attribute__((aligned(16))) bf16_t dOt[D * ColTile<BQ>::kStride];
+    __shared__ float lse_s[BQ], delta_s[BQ];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int bh = blockIdx.y;
+    const int N = a.N;
+    const KvItem item = a.items[blockIdx.x];
+
+    const T *qbase = static_cast<const T *>(a.q) + (size_t)bh * N * D;
+    const T *kbase = static_cast<const T *>(a.k) + (size_t)bh * N * D;
+    const T *vbase = static_cast<const T *>(a.v) + (size_t)bh * N * D;
+    const T *dobase = static_cast<const T *>(a.d_o) + (size_t)bh * N * D;
+    const float *lse = a.lse + (size_t)bh * N;
+    const float *delta = a.delta + (size_t)bh * N;
+
+    // this wave's 32 keys (B operands stay in registers for the whole item)
+    const int nk = min(32, item.key_len - wave * 32);
+    const bool wave_active = nk > 0;
+    const int key = wave_active ? item.key_start + wave * 32 + min(l32, nk - 1) : item.key_start;
+    bf16x8 kf[KS], vf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        kf[s] = Io<T>::load8(kbase + (size_t)key * D + s * 16 + half * 8);
+        vf[s] = Io<T>::load8(vbase + (size_t)key * D + s * 16 + half * 8);
+    }
+    f32x16 dkacc[DB], dvacc[DB];
+#pragma unroll
+    for (int b = 0; b < DB; ++b) { dkacc[b] = zero16(); dvacc[b] = zero16(); }
+
+    // query sources: a contiguous range, then (video chunks) the chunk's routed list
+    const int nA = (item.q_len + BQ - 1) / BQ;
+    int cntB = 0;
+    const int32_t *entries = nullptr;
+    if (item.chunk >= 0 && a.topk > 0) {
+        const int32_t *loff = a.list_off + (size_t)bh * (a.C + 1);
+        cntB = loff[item.chunk + 1] - loff[item.chunk];
+        entries = a.qlist + (size_t)bh * N * a.topk + loff[item.chunk];
+    }
+    const int ntiles = nA + (cntB + BQ - 1) / BQ;
+    const int topk = a.topk;
+
+    RowStager<D, T, BQ> qst(tid), dost(tid);
+    ColStager<D, T, BQ> cst(lane, wave & 1);      // waves 0,1: Q^T   waves 2,3: dO^T
+    const T *cbase = wave < 2 ? qbase : dobase;
+    bf16_t *clds = wave < 2 ? Qt : dOt;
+    float lreg = 0.f, dreg = 0.f;
+
+    auto tile_valid = [&](int t) { return t < nA ? min(BQ, item.q_len - t * BQ) : min(BQ, cntB - (t - nA) * BQ); };
+    auto load_tile = [&](int t) {
+        const int nv = tile_valid(t);
+        if (t < nA) {
+            const int q0 = item.q_start + t * BQ;
+            auto fn = [=](int r) { return q0 + min(r, nv - 1); };
+            qst.load_fn(qbase, fn);
+            dost.load_fn(dobase, fn);
+            cst.load_fn(cbase, fn);
+            if (tid < BQ) { const int i = fn(tid); lreg = lse[i]; dreg = delta[i]; }
+        } else {
+            const int32_t *en = entries + (t - nA) * BQ;
+            auto fn = [=](int r) { return en[min(r, nv - 1)] / topk; };
+            qst.load_fn(qbase, fn);
+            dost.load_fn(dobase, fn);
+            cst.load_fn(cbase, fn);
+            if (tid < BQ) { const int i = fn(tid); lreg = lse[i]; dreg = delta[i]; }
+        }
+    };
+
+    const float c = a.scale_log2;
+    if (ntiles > 0) load_tile(0);
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+        qst.store(Qs);
+        dost.store(dOs);
+        cst.store(clds);
+        if (tid < BQ) { lse_s[tid] = lreg * kLog2e; delta_s[tid] = dreg; }
+        __syncthreads();
+        const int nv = tile_valid(t);
+        if (t + 1 < ntiles) load_tile(t + 1);
+        if (wave_active) {
+            // S[query][key], dP[query][key]: lane owns a key column
+            f32x16 sacc = zero16(), dpacc = zero16();
+#pragma unroll
+            for (int s = 0; s < KS; ++s) sacc = mfma32(RowTile<D>::frag(Qs, l32, s, half), kf[s], sacc);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) dpacc = mfma32(RowTile<D>::frag(dOs, l32, s, half), vf[s], dpacc);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = (i >> 2) * 8 + half * 4 + (i & 3);
+                float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, -lse_s[row]));
+                if (row >= nv) p = 0.f;
+                sacc[i] = p;
+                dpacc[i] = p * (dpacc[i] - delta_s[row]);
+            }
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                if (ks * 16 < nv) {
+                    const bf16x8 pf = acc_to_frag(sacc, ks);
+                    const bf16x8 dsf = acc_to_frag(dpacc, ks);
+#pragma unroll
+                    for (int b = 0; b < DB; ++b) {
+                        dvacc[b] = mfma32(ColTile<BQ>::frag(dOt, b * 32 + l32, ks, half), pf, dvacc[b]);
+                        dkacc[b] = mfma32(ColTile<BQ>::frag(Qt, b * 32 + l32, ks, half), dsf, dkacc[b]);
+                    }
+                }
+            }
+        }
+    }
+
+    if (!wave_active || l32 >= nk) return;
+    const float sc = a.scale;
+    if (item.partial < 0) {
+        T *dk = static_cast<T *>(a.dk) + ((size_t)bh * N + key) * D;
+        T *dv = static_cast<T *>(a.dv) + ((size_t)bh * N + key) * D;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int x = b * 32 + g * 8 + half * 4;
+                Io<T>::store4(dk + x, dkacc[b][4 * g] * sc, dkacc[b][4 * g + 1] * sc, dkacc[b][4 * g + 2] * sc,
+                              dkacc[b][4 * g + 3] * sc);
+                Io<T>::store4(dv + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
+            }
+    } else {
+        const size_t prow = ((size_t)bh * a.n_partials + item.partial) * kKeyTile + wave * 32 + l32;
+        float *pk = a.tpart_k + prow * D, *pv = a.tpart_v + prow * D;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int x = b * 32 + g * 8 + half * 4;
+                Io<float>::store4(pk + x, dkacc[b][4 * g] * sc, dkacc[b][4 * g + 1] * sc, dkacc[b][4 * g + 2] * sc,
+                                  dkacc[b][4 * g + 3] * sc);
+                Io<float>::store4(pv + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
+            }
+    }
+}
+
+// sums the per-segment partials of a text key tile in a fixed order
+template <int D, typename T>
+__global__ __launch_bounds__(256) void text_reduce_kernel(const float *__restrict__ tpart_k,
+                                                          const float *__restrict__ tpart_v,
+                                                          const TextTile *__restrict__ tiles, int n_partials, int N,
+                                                          T *__restrict__ dk, T *__restrict__ dv) {
+    const TextTile tt = tiles[blockIdx.x];
+    const int bh = blockIdx.y;
+    constexpr int V4 = D / 4;                       // float4 groups per row
+    for (int u = threadIdx.x; u < tt.key_len * V4; u += 256) {
+        const int kr = u / V4, x = (u % V4) * 4;
+        f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < tt.n_partials; ++p) {
+            const size_t prow = ((size_t)bh * n_partials + tt.first_partial + p) * kKeyTile + kr;
+            sk += *reinterpret_cast<const f32x4 *>(tpart_k + prow * D + x);
+            sv += *reinterpret_cast<const f32x4 *>(tpart_v + prow * D + x);
+        }
+        const size_t row = (size_t)bh * N + tt.key_start + kr;
+        Io<T>::store4(dk + row * D + x, sk[0], sk[1], sk[2], sk[3]);
+        Io<T>::store4(dv + row * D + x, sv[0], sv[1], sv[2], sv[3]);
+    }
+}
+
+template <int D, typename T>
+static hipError_t bwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, KvArgs &kv, const void *o, const int32_t *sel,
+                               void *dq, hipStream_t st) {
+    constexpr int QPW = 256 / (D / 8);
+    const size_t rows = (size_t)BH * m->N;
+    delta_kernel<D, T><<<dim3((unsigned)((rows + QPW - 1) / QPW)), dim3(256), 0, st>>>(
+        static_cast<const T *>(o), static_cast<const T *>(a.d_o), rows, const_cast<float *>(a.delta));
+    attn_bwd_dkdv_kernel<D, T><<<dim3(m->n_kvitems, BH), dim3(256), 0, st>>>(kv);
+    if (m->n_text_tiles > 0)
+        text_reduce_kernel<D, T><<<dim3(m->n_text_tiles, BH), dim3(256), 0, st>>>(
+            kv.tpart_k, kv.tpart_v, m->d_text_tiles, m->n_partials, m->N, static_cast<T *>(kv.dk),
+            static_cast<T *>(kv.dv));
+    if (a.topk > 0) {
+        const int max_tiles = (m->N * a.topk + kBM - 1) / kBM + m->C;
+        attn_bwd_dq_kernel<D, T, MODE_ROUTED><<<dim3(max_tiles, BH), dim3(256), 0, st>>>(a);
+    }
+    attn_bwd_dq_kernel<D, T, MODE_ANCHOR><<<dim3(m->n_atiles, BH), dim3(256), 0, st>>>(a);
+    dq_merge_kernel<D, T><<<dim3((m->N + QPW - 1) / QPW, BH), dim3(256), 0, st>>>(a.po, sel, m->N, m->C, a.topk,
+                                                                                static_cast<T *>(dq));
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *k, const void *v,
+                           const void *o, const float *lse, const void *d_o, const int32_t *sel, int topk, float scale,
+                           void *dq, void *dk, void *dv, char *ws, const AttnWs &L, hipStream_t st) {
+    FwdArgs a{};
+    a.q = q; a.k = k; a.v = v; a.d_o = d_o;
+    a.po = reinterpret_cast<bf16_t *>(ws + L.po);
+    a.plse = nullptr;
+    a.N = m->N; a.C = m->C; a.topk = topk; a.slots = topk + 1;
+    a.scale = scale; a.scale_log2 = scale * kLog2e;
+    a.atiles = m->d_atiles; a.arange_off = m->d_arange_off; a.aranges = m->d_aranges;
+    a.off = m->d_off;
+    a.list_off = reinterpret_cast<const int32_t *>(ws + L.list_off);
+    a.tile_off = reinterpret_cast<const int32_t *>(ws + L.tile_off);
+    a.qlist = reinterpret_cast<const int32_t *>(ws + L.qlist);
+    a.lse = lse;
+    a.delta = reinterpret_cast<const float *>(ws + L.delta);
+    KvArgs kv{};
+    kv.q = q; kv.k = k; kv.v = v; kv.d_o = d_o;
+    kv.lse = lse; kv.delta = a.delta;
+    kv.dk = dk; kv.dv = dv;
+    kv.tpart_k = reinterpret_cast<float *>(ws + L.tpart_k);
+    kv.tpart_v = reinterpret_cast<float *>(ws + L.tpart_v);
+    kv.items = m->d_kvitems;
+    kv.list_off = a.list_off; kv.qlist = a.qlist;
+    kv.N = m->N; kv.C = m->C; kv.topk = topk; kv.n_partials = m->n_partials;
+    kv.scale = scale; kv.scale_log2 = a.scale_log2;
+    if (dtype == MOC_BF16) return d == 128 ? bwd_dispatch<128, bf16_t>(m, BH, a, kv, o, sel, dq, st)
+                                           : bwd_dispatch<64, bf16_t>(m, BH, a, kv, o, sel, dq, st);
+    return d == 128 ? bwd_dispatch<128, float>(m, BH, a, kv, o, sel, dq, st)
+                    : bwd_dispatch<64, float>(m, BH, a, kv, o, sel, dq, st);
+}
+
+}  // namespace moc

@@ -1,0 +1,162 @@
+// Work-item decoding and global->LDS staging shared by the attention passes.
+#pragma once
+#include "moc_device.h"
+#include "moc_internal.h"
+
+namespace moc {
+
+constexpr int MODE_ANCHOR = 0;  // forced links: window query tile x (text spans + window)
+constexpr int MODE_ROUTED = 1;  // routed links: gathered queries of a chunk x that chunk
+
+// Arguments of the query-stationary passes (forward, and dQ of the backward).
+struct FwdArgs {
+    const void *q, *k, *v;
+    bf16_t *po;        // [BH, N, slots, D] partial outputs (forward) / partial dQ (backward)
+    float *plse;       // [BH, N, slots]   partial log-sum-exp (forward only)
+    int N, C, topk, slots;
+    float scale, scale_log2;
+    const AnchorTile *atiles;
+    const int32_t *arange_off;
+    const KeyRange *aranges;
+    const int32_t *off, *list_off, *tile_off, *qlist;
+    // backward only
+    const void *d_o;
+    const float *lse, *delta;
+};
+
+struct ItemDesc {
+    int q_start, q_count;
+    const int32_t *entries;   // gathered rows (flat sel indices) or nullptr
+    int nranges;
+    const KeyRange *ranges;   // nullptr: use `single`
+    KeyRange single;
+    __device__ __forceinline__ KeyRange range(int r) const { return ranges ? ranges[r] : single; }
+};
+
+template <int MODE>
+__device__ __forceinline__ bool decode_item(const FwdArgs &a, int bh, int t, ItemDesc &it) {
+    if (MODE == MODE_ANCHOR) {
+        const AnchorTile at = a.atiles[t];
+        it.q_start = at.q_start;
+        it.q_count = at.q_count;
+        it.entries = nullptr;
+        const int r0 = a.arange_off[at.win];
+        it.nranges = a.arange_off[at.win + 1] - r0;
+        it.ranges = a.aranges + r0;
+        it.single = KeyRange{0, 0};
+        return true;
+    } else {
+        const int C = a.C;
+        const int32_t *toff = a.tile_off + (size_t)bh * (C + 1);
+        if (t >= toff[C]) return false;
+        int lo = 0, hi = C;   // largest j with toff[j] <= t
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (toff[mid] <= t) lo = mid; else hi = mid;
+        }
+        const int j = lo;
+        const int32_t *loff = a.list_off + (size_t)bh * (C + 1);
+        const int tl = t - toff[j];
+        const int cnt = loff[j + 1] - loff[j];
+        it.q_start = 0;
+        it.q_count = min(kBM, cnt - tl * kBM);
+        it.entries = a.qlist + (size_t)bh * a.N * a.topk + loff[j] + tl * kBM;
+        it.nranges = 1;
+        it.ranges = nullptr;
+        it.single = KeyRange{a.off[j], a.off[j + 1] - a.off[j]};
+        return true;
+    }
+}
+
+// Walks the key ranges of an item in tiles of BN keys; the last tile of every
+// range may be ragged (valid() < BN).
+template <int BN> struct TileIter {
+    const ItemDesc &it;
+    int r, pos;
+    KeyRange cur;
+    __device__ __forceinline__ explicit TileIter(const ItemDesc &d) : it(d), r(0), pos(0), cur(d.range(0)) {}
+    __device__ __forceinline__ int start() const { return cur.start + pos; }
+    __device__ __forceinline__ int valid() const { return min(BN, cur.len - pos); }
+    __device__ __forceinline__ bool next() {
+        pos += BN;
+        if (pos >= cur.len) {
+            ++r;
+            pos = 0;
+            if (r >= it.nranges) return false;
+            cur = it.range(r);
+        }
+        return true;
+    }
+};
+
+// Stages ROWS source rows of D features into a row-major LDS tile
+// (RowTile<D>), 16 bytes per lane and pass, through registers so the global
+// loads of the next tile overlap the math on the current one.
+// rowfn(r) gives the global row of tile row r (clamped by the caller).
+template <int D, typename T, int ROWS> struct RowStager {
+    static constexpr int CG = D / 8, RPP = 256 / CG, P = (ROWS + RPP - 1) / RPP;
+    int cg, rr;
+    bf16x8 reg[P];
+    __device__ __forceinline__ explicit RowStager(int tid) : cg(tid % CG), rr(tid / CG) {}
+    template <typename F> __device__ __forceinline__ void load_fn(const T *base, F rowfn) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int row = rr + p * RPP;
+            if (ROWS % RPP == 0 || row < ROWS) reg[p] = Io<T>::load8(base + (size_t)rowfn(row) * D + cg * 8);
+        }
+    }
+    __device__ __forceinline__ void load(const T *base, int start, int valid) {
+        load_fn(base, [=](int r) { return start + min(r, valid - 1); });
+    }
+    __device__ __forceinline__ void store(bf16_t *lds) const {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int row = rr + p * RPP;
+            if (ROWS % RPP == 0 || row < ROWS)
+                *reinterpret_cast<u32x4 *>(lds + row * RowTile<D>::kStride + cg * 8) = __builtin_bit_cast(u32x4, reg[p]);
+        }
+    }
+};
+
+// Stages COLS source rows transposed into ColTile<COLS> ([D][COLS+4]): a lane
+// loads 8 features of 4 consecutive source rows and writes eight 8-byte
+// column pieces. The lane -> (row group, feature group) map keeps the writes
+// of each 32-lane phase on distinct banks. `wv` is the wave's index among the
+// waves that take part; lanes with no unit do nothing (active == false).
+template <int D, typename T, int COLS> struct ColStager {
+    static constexpr int A = COLS / 4, G = D / 8;
+    static_assert(A == 16 || A == 8, "COLS must be 64 or 32");
+    int a, g;
+    bool active;
+    bf16x8 reg[4];
+    __device__ __forceinline__ ColStager(int lane, int wv) {
+        if (A == 16) {
+            const int gs = lane >> 4;
+            a = lane & 15;
+            g = (((gs & 1) << 1) | (gs >> 1)) + 4 * wv;
+        } else {
+            a = lane & 7;
+            g = (lane >> 3) + 8 * wv;
+        }
+        active = g < G && wv >= 0;
+    }
+    __device__ __forceinline__ explicit ColStager(int tid) : ColStager(tid & 63, tid >> 6) {}
+    template <typename F> __device__ __forceinline__ void load_fn(const T *base, F rowfn) {
+        if (!active) return;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) reg[kk] = Io<T>::load8(base + (size_t)rowfn(4 * a + kk) * D + g * 8);
+    }
+    __device__ __forceinline__ void load(const T *base, int start, int valid) {
+        load_fn(base, [=](int r) { return start + min(r, valid - 1); });
+    }
+    __device__ __forceinline__ void store(bf16_t *lds) const {
+        if (!active) return;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            bf16x4 t = {reg[0][e], reg[1][e], reg[2][e], reg[3][e]};
+            *reinterpret_cast<u32x2 *>(lds + (8 * g + e) * ColTile<COLS>::kStride + 4 * a) = __builtin_bit_cast(u32x2, t);
+        }
+    }
+};
+
+}  // namespace moc

@@ -1,0 +1,232 @@
+// Stage (d) forward: routed softmax attention (Eq. 2) on bf16 matrix cores.
+//
+// Work is split into two kinds of dense items, both "a tile of <= 128 query
+// rows against contiguous key ranges":
+//   forced-link items  queries of one window tile x (all text spans + the window)
+//   routed items       queries gathered through a chunk's inverse list x that chunk
+// Every item produces a normalised partial output and its log-sum-exp in the
+// slot of the (query, link) pair; a merge kernel combines the <= topk+1 partials
+// of a query (the usual split-softmax identity), so no item ever waits on another.
+//
+// Per workgroup: 4 waves x 32 query rows. K tiles (64 keys) are staged row-major
+// and V tiles transposed in LDS; S^T = K Q^T and O^T = V^T P^T are computed so
+// that each lane owns one query column: softmax statistics are per-lane scalars
+// and the S^T accumulator feeds the second product without any shuffle.
+#include "moc_attn_common.h"
+
+namespace moc {
+
+template <int D, typename T, int MODE>
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
+    constexpr int BN = 64;
+    constexpr int KS = D / 16;   // feature steps of the QK product
+    constexpr int DB = D / 32;   // 32-feature blocks of the output
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[BN * RowTile<D>::kStride];
+    __shared__ __attribute__((aligned(16))) bf16_t Vt[D * ColTile<BN>::kStride];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int bh = blockIdx.y;
+    const int N = a.N;
+
+    ItemDesc it;
+    if (!decode_item<MODE>(a, bh, blockIdx.x, it)) return;
+
+    // ---- this lane's query row
+    const int r = wave * 32 + l32;
+    const bool row_valid = r < it.q_count;
+    const bool wave_active = wave * 32 < it.q_count;
+    const int rc = row_valid ? r : it.q_count - 1;
+    int qi, slot;
+    if (MODE == MODE_ANCHOR) { qi = it.q_start + rc; slot = a.topk; }
+    else { const int e = it.entries[rc]; qi = e / a.topk; slot = e - qi * a.topk; }
+
+    const T *qbase = static_cast<const T *>(a.q) + (size_t)bh * N * D;
+    const T *kbase = static_cast<const T *>(a.k) + (size_t)bh * N * D;
+    const T *vbase = static_cast<const T *>(a.v) + (size_t)bh * N * D;
+
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qf[s] = Io<T>::load8(qbase + (size_t)qi * D + s * 16 + half * 8);
+
+    f32x16 oacc[DB];
+#pragma unroll
+    for (int b = 0; b < DB; ++b) oacc[b] = zero16();
+    float m_run = -INFINITY, l_run = 0.f;
+    const float c = a.scale_log2;
+
+    RowStager<D, T, BN> kst(tid);
+    ColStager<D, T, BN> vst(tid);
+    TileIter<BN> ti(it);
+    kst.load(kbase, ti.start(), ti.valid());
+    vst.load(vbase, ti.start(), ti.valid());
+    while (true) {
+        __syncthreads();
+        kst.store(Ks);
+        vst.store(Vt);
+        __syncthreads();
+        const int valid = ti.valid();
+        const bool more = ti.next();
+        if (more) {
+            kst.load(kbase, ti.start(), ti.valid());
+            vst.load(vbase, ti.start(), ti.valid());
+        }
+        if (wave_active) {
+            // S^T[key][query]
+            f32x16 sacc[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                sacc[kb] = zero16();
+                if (kb * 32 < valid) {
+#pragma unroll
+                    for (int s = 0; s < KS; ++s)
+                        sacc[kb] = mfma32(RowTile<D>::frag(Ks, kb * 32 + l32, s, half), qf[s], sacc[kb]);
+                }
+            }
+            if (valid < BN) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = kb * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
+                        if (key >= valid) sacc[kb][i] = -INFINITY;
+                    }
+            }
+            // online softmax over this lane's 32 keys, then across the two halves
+            float mx = sacc[0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
+            mx = fmaxf(mx, xhalf(mx));
+            const float m_new = fmaxf(m_run, mx);
+            if (__any(m_new > m_run)) {
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+                l_run *= alpha;
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+                m_run = m_new;
+            }
+            const float mc = m_run * c;
+            float ls = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], c, -mc));
+                    sacc[kb][i] = p;
+                    ls += p;
+                }
+            l_run += ls;
+            // O^T[feature][query] += V^T P^T
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks * 16 < valid) {
+                    const bf16x8 pf = acc_to_frag(sacc[ks >> 1], ks & 1);
+#pragma unroll
+                    for (int b = 0; b < DB; ++b)
+                        oacc[b] = mfma32(ColTile<BN>::frag(Vt, b * 32 + l32, ks, half), pf, oacc[b]);
+                }
+            }
+        }
+        if (!more) break;
+    }
+
+    if (!row_valid) return;
+    const float l_tot = l_run + xhalf(l_run);
+    const float inv = 1.f / l_tot;
+    const size_t prow = ((size_t)bh * N + qi) * a.slots + slot;
+    bf16_t *po = a.po + prow * D;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int x = b * 32 + g * 8 + half * 4;
+            Io<bf16_t>::store4(po + x, oacc[b][4 * g] * inv, oacc[b][4 * g + 1] * inv, oacc[b][4 * g + 2] * inv,
+                               oacc[b][4 * g + 3] * inv);
+        }
+    if (half == 0) a.plse[prow] = m_run * a.scale + __logf(l_tot);
+}
+
+// o = sum_s exp(lse_s - lse) o_s over the forced-link slot and the used routed slots
+template <int D, typename T>
+__global__ __launch_bounds__(256) void fwd_merge_kernel(const bf16_t *__restrict__ po,
+                                                        const float *__restrict__ plse,
+                                                        const int32_t *__restrict__ sel, int N, int C, int topk,
+                                                        T *__restrict__ o, float *__restrict__ lse) {
+    constexpr int TPQ = D / 8, QPW = 256 / TPQ;
+    const int bh = blockIdx.y;
+    const int i = blockIdx.x * QPW + threadIdx.x / TPQ;
+    const int c8 = threadIdx.x % TPQ;
+    if (i >= N) return;
+    const int slots = topk + 1;
+    const size_t row = (size_t)bh * N + i;
+    const float *pl = plse + row * slots;
+    const int32_t *sr = sel + row * topk;
+    float mx = pl[topk];
+    for (int s = 0; s < topk; ++s) {
+        const int j = sr[s];
+        if (j >= 0 && j < C) mx = fmaxf(mx, pl[s]);
+    }
+    float z = __expf(pl[topk] - mx);
+    for (int s = 0; s < topk; ++s) {
+        const int j = sr[s];
+        if (j >= 0 && j < C) z += __expf(pl[s] - mx);
+    }
+    const float tot = mx + __logf(z);
+    float acc[8], f[8];
+    {
+        const float w = __expf(pl[topk] - tot);
+        Io<bf16_t>::load8f(po + (row * slots + topk) * D + c8 * 8, f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = w * f[e];
+    }
+    for (int s = 0; s < topk; ++s) {
+        const int j = sr[s];
+        if (j >= 0 && j < C) {
+            const float w = __expf(pl[s] - tot);
+            Io<bf16_t>::load8f(po + (row * slots + s) * D + c8 * 8, f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(w, f[e], acc[e]);
+        }
+    }
+    Io<T>::store8(o + row * D + c8 * 8, acc);
+    if (c8 == 0) lse[row] = tot;
+}
+
+template <int D, typename T>
+static hipError_t fwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, const int32_t *sel, void *o, float *lse,
+                               hipStream_t st) {
+    if (a.topk > 0) {
+        const int max_tiles = (m->N * a.topk + kBM - 1) / kBM + m->C;
+        attn_fwd_kernel<D, T, MODE_ROUTED><<<dim3(max_tiles, BH), dim3(256), 0, st>>>(a);
+    }
+    attn_fwd_kernel<D, T, MODE_ANCHOR><<<dim3(m->n_atiles, BH), dim3(256), 0, st>>>(a);
+    constexpr int QPW = 256 / (D / 8);
+    fwd_merge_kernel<D, T><<<dim3((m->N + QPW - 1) / QPW, BH), dim3(256), 0, st>>>(
+        a.po, a.plse, sel, m->N, m->C, a.topk, static_cast<T *>(o), lse);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_fwd(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *k, const void *v,
+                           const int32_t *sel, int topk, float scale, void *o, float *lse, char *ws, const AttnWs &L,
+                           hipStream_t st) {
+    FwdArgs a{};
+    a.q = q; a.k = k; a.v = v;
+    a.po = reinterpret_cast<bf16_t *>(ws + L.po);
+    a.plse = reinterpret_cast<float *>(ws + L.plse);
+    a.N = m->N; a.C = m->C; a.topk = topk; a.slots = topk + 1;
+    a.scale = scale; a.scale_log2 = scale * kLog2e;
+    a.atiles = m->d_atiles; a.arange_off = m->d_arange_off; a.aranges = m->d_aranges;
+    a.off = m->d_off;
+    a.list_off = reinterpret_cast<const int32_t *>(ws + L.list_off);
+    a.tile_off = reinterpret_cast<const int32_t *>(ws + L.tile_off);
+    a.qlist = reinterpret_cast<const int32_t *>(ws + L.qlist);
+    if (dtype == MOC_BF16) return d == 128 ? fwd_dispatch<128, bf16_t>(m, BH, a, sel, o, lse, st)
+                                           : fwd_dispatch<64, bf16_t>(m, BH, a, sel, o, lse, st);
+    return d == 128 ? fwd_dispatch<128, float>(m, BH, a, sel, o, lse, st)
+                    : fwd_dispatch<64, float>(m, BH, a, sel, o, lse, st);
+}
+
+}  // namespace moc

@@ -1,0 +1,137 @@
+// Device-side building blocks shared by the MoC kernels (gfx950 only).
+//
+// MFMA operand/accumulator layouts used throughout (wave64):
+//   v_mfma_f32_32x32x16_bf16  D[32x32] += A[32x16] * B[16x32]
+//     A operand: lane l holds A[l%32][8*(l/32) .. +8]          (8 bf16 = 4 VGPRs)
+//     B operand: lane l holds B[8*(l/32) .. +8][l%32]
+//     accumulator: lane l, register i (0..15) holds
+//                  D[(i/4)*8 + (l/32)*4 + i%4][l%32]
+// A contraction index may be permuted freely as long as A and B use the same
+// permutation; the kernels use that to feed an accumulator tile straight back
+// in as the B operand of the next product (see acc_to_bfrag).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moc {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] = 0.f;
+    return z;
+}
+
+// two floats -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    bf16x2 p = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, p);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// Registers 8*s .. 8*s+7 of a 32x32 accumulator as one B (or A) operand whose
+// contraction slot e of lane-half h corresponds to accumulator row
+//   (2*s + e/4)*8 + 4*h + e%4.
+__device__ __forceinline__ bf16x8 acc_to_frag(const f32x16 &acc, int s) {
+    u32x4 r;
+    r[0] = pack_bf16(acc[8 * s + 0], acc[8 * s + 1]);
+    r[1] = pack_bf16(acc[8 * s + 2], acc[8 * s + 3]);
+    r[2] = pack_bf16(acc[8 * s + 4], acc[8 * s + 5]);
+    r[3] = pack_bf16(acc[8 * s + 6], acc[8 * s + 7]);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// 8 consecutive elements of a row, converted to bf16 if the storage is fp32.
+template <typename T> struct Io;
+template <> struct Io<bf16_t> {
+    static __device__ __forceinline__ bf16x8 load8(const bf16_t *p) {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p));
+    }
+    static __device__ __forceinline__ void load8f(const bf16_t *p, float *f) {
+        u32x4 u = *reinterpret_cast<const u32x4 *>(p);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { f[2 * i] = bf16_lo(u[i]); f[2 * i + 1] = bf16_hi(u[i]); }
+    }
+    static __device__ __forceinline__ void store4(bf16_t *p, float a, float b, float c, float d) {
+        u32x2 u = {pack_bf16(a, b), pack_bf16(c, d)};
+        *reinterpret_cast<u32x2 *>(p) = u;
+    }
+    static __device__ __forceinline__ void store8(bf16_t *p, const float *f) {
+        u32x4 u = {pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
+        *reinterpret_cast<u32x4 *>(p) = u;
+    }
+};
+template <> struct Io<float> {
+    static __device__ __forceinline__ bf16x8 load8(const float *p) {
+        f32x4 a = *reinterpret_cast<const f32x4 *>(p);
+        f32x4 b = *reinterpret_cast<const f32x4 *>(p + 4);
+        u32x4 r = {pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]), pack_bf16(b[2], b[3])};
+        return __builtin_bit_cast(bf16x8, r);
+    }
+    static __device__ __forceinline__ void load8f(const float *p, float *f) {
+        f32x4 a = *reinterpret_cast<const f32x4 *>(p);
+        f32x4 b = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { f[i] = a[i]; f[4 + i] = b[i]; }
+    }
+    static __device__ __forceinline__ void store4(float *p, float a, float b, float c, float d) {
+        f32x4 u = {a, b, c, d};
+        *reinterpret_cast<f32x4 *>(p) = u;
+    }
+    static __device__ __forceinline__ void store8(float *p, const float *f) {
+        f32x4 a = {f[0], f[1], f[2], f[3]}, b = {f[4], f[5], f[6], f[7]};
+        *reinterpret_cast<f32x4 *>(p) = a;
+        *reinterpret_cast<f32x4 *>(p + 4) = b;
+    }
+};
+
+// exchange with the other half-wave (lane ^ 32)
+__device__ __forceinline__ float xhalf(float v) { return __shfl_xor(v, 32, 64); }
+
+// Row-major LDS tile [ROWS][D + 8] of bf16 (row stride (D+8)*2 bytes keeps the
+// 16-byte operand reads of 16 consecutive rows on distinct banks).
+template <int D> struct RowTile {
+    static constexpr int kStride = D + 8;
+    // operand fragment: row r, contraction elements [16*step + 8*half, +8)
+    static __device__ __forceinline__ bf16x8 frag(const bf16_t *base, int r, int step, int half) {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + r * kStride + step * 16 + half * 8));
+    }
+};
+
+// Transposed LDS tile [D][COLS + 4]: element (x, c) = source row c, feature x.
+// Row stride (COLS+4)*2 bytes: the 8-byte reads of 32 consecutive feature rows
+// fall on distinct bank pairs when COLS is a multiple of 64.
+template <int COLS> struct ColTile {
+    static constexpr int kStride = COLS + 4;
+    // operand fragment for contraction step s (16 source rows) in the permuted
+    // order of acc_to_frag: slots 0..3 -> rows 16s + 4h + {0..3}, slots 4..7 -> +8.
+    static __device__ __forceinline__ bf16x8 frag(const bf16_t *base, int x, int s, int half) {
+        const bf16_t *p = base + x * kStride + 16 * s + 4 * half;
+        u32x2 a = *reinterpret_cast<const u32x2 *>(p);
+        u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
+        u32x4 r = {a[0], a[1], b[0], b[1]};
+        return __builtin_bit_cast(bf16x8, r);
+    }
+};
+
+}  // namespace moc

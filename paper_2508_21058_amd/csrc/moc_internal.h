@@ -1,0 +1,86 @@
+// Host-side structures and kernel launchers of libmoc (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/moc.h"
+
+namespace moc {
+
+constexpr int kBM = 128;         // queries per workgroup in the query-stationary passes
+constexpr int kKeyTile = 128;    // keys per workgroup in the key-stationary pass (4 waves x 32)
+constexpr int kTextSeg = 4096;   // queries per partial of a text key tile in the key-stationary pass
+
+// One query tile of the forced-link pass: queries [q_start, q_start+q_count)
+// all belong to window `win` and share its key ranges.
+struct AnchorTile { int32_t q_start, q_count, win, pad; };
+
+// A contiguous key range [start, start+len).
+struct KeyRange { int32_t start, len; };
+
+// One workgroup of the key-stationary backward pass.
+//   keys [key_start, key_start+key_len), key_len <= kKeyTile
+//   contiguous query source [q_start, q_start+q_len)
+//   chunk >= 0: additionally the routed-query list of that chunk
+//   partial >= 0: write fp32 partial sums to that slot instead of dk/dv
+struct KvItem { int32_t key_start, key_len, q_start, q_len, chunk, partial, pad0, pad1; };
+
+// A text key tile and the partial slots to sum for it.
+struct TextTile { int32_t key_start, key_len, first_partial, n_partials; };
+
+}  // namespace moc
+
+struct moc_meta {
+    int32_t N = 0, C = 0, T = 0, W = 0;
+    int32_t n_atiles = 0, n_ranges = 0, n_kvitems = 0, n_text_tiles = 0, n_partials = 0;
+    void *d_base = nullptr;
+    size_t d_bytes = 0;
+    int32_t *d_off = nullptr;        // [C+1]
+    int32_t *d_kind = nullptr;       // [C] 1 = text
+    int32_t *d_win = nullptr;        // [C] dense window id
+    int32_t *d_wfirst = nullptr;     // [W] first chunk of window
+    int32_t *d_wlast = nullptr;      // [W] last chunk of window (inclusive)
+    int32_t *d_chunk_of = nullptr;   // [N]
+    int32_t *d_arange_off = nullptr; // [W+1] into d_aranges
+    moc::KeyRange *d_aranges = nullptr;
+    moc::AnchorTile *d_atiles = nullptr;
+    moc::KvItem *d_kvitems = nullptr;
+    moc::TextTile *d_text_tiles = nullptr;
+    std::vector<int32_t> h_off, h_kind, h_win;
+};
+
+namespace moc {
+
+// Layout of the attention workspace (byte offsets); shared by fwd and bwd.
+struct AttnWs {
+    size_t cnt, list_off, tile_off, cursor, qlist, plse, po, delta, tpart_k, tpart_v, total;
+};
+AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd);
+
+struct RouteWs { size_t total; };
+RouteWs route_ws_layout(const moc_meta *m, int BH, int d, int topk, int dtype);
+
+hipError_t launch_chunk_of(const moc_meta *m, hipStream_t st);
+
+hipError_t launch_pool(const moc_meta *m, int BH, int d, int dtype, const void *k, float *kbar, hipStream_t st);
+
+hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void *q, const float *kbar,
+                        int topk, int causal, int32_t *sel, hipStream_t st);
+
+// counts -> offsets -> inverse lists (per head and chunk: the queries that routed to it)
+hipError_t launch_build_lists(const moc_meta *m, int BH, int topk, const int32_t *sel, char *ws,
+                              const AttnWs &L, hipStream_t st);
+
+hipError_t launch_attn_fwd(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *k,
+                           const void *v, const int32_t *sel, int topk, float scale, void *o, float *lse,
+                           char *ws, const AttnWs &L, hipStream_t st);
+
+hipError_t launch_attn_bwd(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *k,
+                           const void *v, const void *o, const float *lse, const void *d_o,
+                           const int32_t *sel, int topk, float scale, void *dq, void *dk, void *dv,
+                           char *ws, const AttnWs &L, hipStream_t st);
+
+}  // namespace moc
