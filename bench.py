@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoC attention hot path on ONE MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload eight|single|tiny] [--window frame|shot]
+
+A step is one pass of the hot path over one synthetic batch resident in HBM:
+moc_route (mean pooling, scores, top-k) -> moc_attn_fwd -> moc_attn_bwd.
+moc_chunk_meta depends on the layout only and is built once per layout; its
+time is reported separately (meta_ms).
+
+Prints ONE JSON line. `value` = algorithmic routed-attention FLOPs, forward +
+backward (3.5 x 4 d sum_i |Omega(i)| per head, attended pairs only), divided by
+the whole step time. `roofline` describes the kernel with the largest share of
+the step, timed with HIP events on the launch stream during the timed steps.
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def layout_counts(lay, sel, chunk_of_t, topk):
+    """Attended (query, key) pairs per head-sum, split into forced and routed, and
+    the number of routing candidates - all from the layout and the selection."""
+    import torch
+    off = lay.offsets.astype(np.int64)
+    C = lay.C
+    lens = np.diff(off)
+    is_text = np.zeros(C, bool)
+    for s, e in lay.text_spans.reshape(-1, 2):
+        is_text |= (off[:-1] >= s) & (off[1:] <= e)
+    win = lay.window.astype(np.int64)
+    text_total = int(lens[is_text].sum())
+    # forced keys of a window: all text + the window's non-text tokens
+    wids, winv = np.unique(win, return_inverse=True)
+    win_nontext = np.bincount(winv, weights=lens * (~is_text), minlength=len(wids))
+    forced_per_chunk = text_total + win_nontext[winv]            # per chunk of the query
+    forced_pairs = float((forced_per_chunk * lens).sum())         # per head
+    dev = sel.device
+    lens_t = torch.from_numpy(lens).to(dev)
+    routed_pairs = float((lens_t[sel.clamp(min=0).long()] * (sel >= 0)).sum().item())   # all heads
+    # candidates: earlier chunks that are neither text nor in the own window
+    nontext_before = np.concatenate([[0], np.cumsum(~is_text)])[:-1]
+    first_of_win = np.zeros(len(wids), np.int64)
+    for w in range(len(wids)):
+        first_of_win[w] = np.nonzero(winv == w)[0][0]
+    own_before = np.array([np.sum((~is_text)[first_of_win[winv[c]]:c]) for c in range(C)])
+    elig_per_chunk = nontext_before - own_before
+    eligible = float((elig_per_chunk * lens).sum())               # per head
+    return forced_pairs, routed_pairs, eligible
+
+
+def cpu_baseline(lay, cfg, q, k, v, d_o, topk, budget_queries):
+    """Oracle on one head: the queries that attend two sampled video chunks plus
+    random queries up to `budget_queries`: forward + dQ for those queries, dK/dV
+    for the sampled chunks. Algorithmic FLOPs as for the GPU path."""
+    from oracle import moc_oracle as mo
+    L = mo.OracleLayout.from_layout(lay)
+    N, d = lay.N, cfg["d"]
+    f64 = lambda t: t[0:1, 0:1].float().cpu().numpy().astype(np.float64)
+    qn, kn, vn, don = f64(q), f64(k), f64(v), f64(d_o)
+    rng = np.random.default_rng(0)
+    t0 = time.perf_counter()
+    kbar = mo.pool(L, kn)
+    sel_all, _ = mo.route(L, qn, kbar, topk, True)
+    t_route = time.perf_counter() - t0
+    video = np.nonzero(L.kind == 0)[0]
+    chunks = np.sort(rng.choice(video[len(video) // 4:], size=min(2, len(video)), replace=False)).astype(np.int32)
+    att = np.zeros(N, bool)
+    for j in chunks:
+        att |= (L.win[L.chunk_of] == L.win[j]) | (sel_all[0, 0] == j).any(-1)
+    extra = rng.choice(N, size=min(N, budget_queries), replace=False)
+    att[extra[: max(0, budget_queries - int(att.sum()))]] = True
+    qidx = np.nonzero(att)[0].astype(np.int32)
+    sel_s = sel_all[:, :, qidx]
+    t0 = time.perf_counter()
+    o, lse, pairs_q = mo.attn_fwd(L, qn, kn, vn, sel_s, None, qidx)
+    dq = mo.attn_bwd_dq(L, qn, kn, vn, sel_s, o, lse, don[:, :, qidx], None, qidx)
+    o_full = np.zeros((1, 1, N, d)); o_full[0, 0, qidx] = o[0, 0]
+    lse_full = np.zeros((1, 1, N)); lse_full[0, 0, qidx] = lse[0, 0]
+    mo.attn_bwd_dkdv(L, qn, kn, vn, sel_all, o_full, lse_full, don, None, chunks)
+    dt = time.perf_counter() - t0
+    pairs_k = 0
+    for j in chunks:
+        n_att = int(((L.win[L.chunk_of] == L.win[j]) | (sel_all[0, 0] == j).any(-1)).sum())
+        pairs_k += n_att * int(L.off[j + 1] - L.off[j])
+    flops = 2.0 * d * (3 * pairs_q + 4 * pairs_k)
+    return dict(value=flops / dt / 1e12, unit="TFLOP/s", cores=int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
+                kind="oracle",
+                sample=f"head 0 of the workload: fwd + dQ for {len(qidx)} queries, dK/dV for video chunks "
+                       f"{chunks.tolist()} ({pairs_q} + {pairs_k} attended pairs, {dt:.1f} s; "
+                       f"pool + route of all {N} queries took another {t_route:.1f} s, not counted)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="eight", choices=["eight", "single", "tiny", "sweep"])
+    ap.add_argument("--window", default=None, choices=[None, "frame", "shot", "chunk"])
+    ap.add_argument("--chunk", type=int, default=None)
+    ap.add_argument("--topk", type=int, default=None)
+    ap.add_argument("--cpu-queries", type=int, default=6000, help="oracle sample size (0 = skip the CPU baseline)")
+    ap.add_argument("--seed", type=int, default=1234)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (heads are independent: shard heads across GPUs with no "
+              "collective inside the layer); --gpus must be 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import moc_inputs as mi
+    from paper_2508_21058_amd import binding as mb
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    cfg = dict(mi.CONFIGS[args.workload])
+    if args.topk is not None:
+        cfg["topk"] = args.topk
+    lay = mi.config_layout(args.workload, window=args.window, chunk=args.chunk)
+    B, H, d, topk, N = cfg["B"], cfg["H"], cfg["d"], cfg["topk"], lay.N
+    tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    q, k, v, d_o = (t.to(tdt).contiguous() for t in mi.qkv_do(B, H, N, d, args.seed, "cuda"))
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
+    torch.cuda.synchronize()
+    meta_ms = (time.perf_counter() - t0) * 1e3
+
+    ws = mb.attn_workspace(meta, B, H, d, topk, tdt, True)
+    o = torch.empty_like(q); lse = torch.empty(B, H, N, dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        pooled, sel = mb.route(meta, q, k, topk, True)
+        if ev: ev[1].record()
+        mb.attn_fwd(meta, q, k, v, sel, None, ws, (o, lse))
+        if ev: ev[2].record()
+        mb.attn_bwd(meta, q, k, v, o, lse, d_o, sel, None, ws, (dq, dk, dv))
+        if ev: ev[3].record()
+        return sel
+
+    for _ in range(args.warmup):
+        sel = step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    mb.prof_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        sel = step(evs[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern = mb.prof_read()
+    mb.prof_enable(False)
+    ms_step = wall * 1e3 / args.steps
+    stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in evs]).mean(0)
+
+    forced_pairs, routed_pairs, eligible = layout_counts(lay, sel, None, topk)
+    BH = B * H
+    pairs_f, pairs_r = forced_pairs * BH, routed_pairs
+    pairs = pairs_f + pairs_r
+    fwd_flops = 4.0 * d * pairs
+    total_flops = 3.5 * fwd_flops
+    esz = 2 if tdt == torch.bfloat16 else 4
+    # algorithmic work per kernel launch: (kind, amount)
+    alg = {
+        "attn_fwd_forced": ("flop", 4.0 * d * pairs_f), "attn_fwd_routed": ("flop", 4.0 * d * pairs_r),
+        "attn_bwd_dkdv": ("flop", 8.0 * d * pairs),
+        "attn_bwd_dq_forced": ("flop", 2.0 * d * pairs_f), "attn_bwd_dq_routed": ("flop", 2.0 * d * pairs_r),
+        "pool": ("byte", BH * (N * d * esz + lay.C * d * 4.0)),
+        "route_topk": ("byte", BH * (N * d * esz + lay.C * d * 4.0 + N * topk * 4.0)),
+    }
+    kernels = {}
+    for name, (cnt, ms) in kern.items():
+        per = ms / max(cnt, 1)
+        row = dict(ms=round(per, 4))
+        if name in alg:
+            kind, amt = alg[name]
+            if kind == "flop":
+                row["tflops"] = round(amt / (per * 1e-3) / 1e12, 2)
+            else:
+                row["gbs"] = round(amt / (per * 1e-3) / 1e9, 1)
+        kernels[name] = row
+    dom = max((n for n in kernels if n in alg), key=lambda n: kernels[n]["ms"])
+    if alg[dom][0] == "flop":
+        ach = alg[dom][1] / (kernels[dom]["ms"] * 1e-3) / 1e12
+        roof = dict(kernel=dom, bound="mfma", achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None, avg_ms=kernels[dom]["ms"])
+    else:
+        ach = alg[dom][1] / (kernels[dom]["ms"] * 1e-3) / 1e9
+        roof = dict(kernel=dom, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, avg_ms=kernels[dom]["ms"])
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tfile):
+        with open(tfile) as f:
+            tr = json.load(f)
+        key = f"{args.workload}:{lay.meta.get('window')}:{dom}"
+        roof["traffic"] = tr.get(key)
+
+    out = {
+        "metric": "routed_attn_tflops_fwd_bwd", "value": round(total_flops / (ms_step * 1e-3) / 1e12, 2),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if tdt == torch.bfloat16 else "f32(bf16 mfma)", "data": "synthetic",
+        "config": {"workload": f"{args.workload} ({lay.name}): B={B} H={H} N={N} d={d} C={lay.C} "
+                               f"chunk={lay.meta.get('chunk')} window={lay.meta.get('window')} topk={topk} causal",
+                   "inputs": "S1 iid N(0,1) rounded to bf16, seeded", "pass": "route + attn fwd + attn bwd"},
+        "frac_of_bf16_mfma_peak": round(total_flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "attn_only_tflops": round(total_flops / ((stage[1] + stage[2]) * 1e-3) / 1e12, 2),
+        "stage_ms": {"route": round(float(stage[0]), 3), "attn_fwd": round(float(stage[1]), 3),
+                     "attn_bwd": round(float(stage[2]), 3), "chunk_meta_once": round(meta_ms, 3)},
+        "keys_per_query": round(pairs / (BH * N), 1), "sparsity": round(1 - pairs / (BH * float(N) * N), 4),
+        "kernels": kernels, "roofline": roof,
+    }
+    if args.cpu_queries > 0:
+        out["cpu_baseline"] = cpu_baseline(lay, cfg, q, k, v, d_o, topk, args.cpu_queries)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

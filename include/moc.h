@@ -146,6 +146,18 @@ int moc_attn_bwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtyp
                  void *dq, void *dk, void *dv, void *workspace, size_t workspace_bytes,
                  void *stream);
 
+/*
+ * Per-kernel timing (measurement aid, not part of the layer). While enabled,
+ * every kernel launch of the library is bracketed by HIP events recorded on the
+ * launch stream. moc_prof_enable(on) clears the records. moc_prof_read(-1, ...)
+ * returns the number of distinct kernels recorded (>= 0); moc_prof_read(i, ...)
+ * waits for the recorded events and returns kernel i's name, launch count and
+ * summed duration in milliseconds. Not thread-safe against concurrent launches
+ * on other streams.
+ */
+int moc_prof_enable(int on);
+int moc_prof_read(int32_t index, char *name, size_t name_cap, int32_t *launches, float *total_ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,8 @@ MOC_BF16, MOC_F32 = 0, 1
 MOC_MAX_TOPK = 32
 
 SYMBOLS = ["moc_status_string", "moc_last_error", "moc_chunk_meta", "moc_meta_destroy", "moc_meta_copy_tables",
-           "moc_route_workspace_bytes", "moc_route", "moc_attn_workspace_bytes", "moc_attn_fwd", "moc_attn_bwd"]
+           "moc_route_workspace_bytes", "moc_route", "moc_attn_workspace_bytes", "moc_attn_fwd", "moc_attn_bwd",
+           "moc_prof_enable", "moc_prof_read"]
 
 
 class MocError(RuntimeError):
@@ -58,6 +59,8 @@ def lib():
     l.moc_attn_fwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, sz, vp]
     l.moc_attn_bwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, i32, C.c_float,
                                vp, vp, vp, vp, sz, vp]
+    l.moc_prof_enable.argtypes = [C.c_int]
+    l.moc_prof_read.argtypes = [i32, C.c_char_p, sz, C.POINTER(i32), C.POINTER(C.c_float)]
     for name in SYMBOLS:
         if name not in ("moc_status_string", "moc_last_error"):
             getattr(l, name).restype = C.c_int
@@ -201,3 +204,21 @@ def attn_bwd(meta: Meta, q, k, v, o, lse, d_o, sel, scale: Optional[float] = Non
                               _ptr(d_o), _ptr(sel) if topk > 0 else None, topk, scale, _ptr(dq), _ptr(dk), _ptr(dv),
                               _ptr(ws), ws.numel(), _stream()), "moc_attn_bwd")
     return dq, dk, dv
+
+
+def prof_enable(on: bool):
+    _check(lib().moc_prof_enable(int(on)), "moc_prof_enable")
+
+
+def prof_read():
+    """-> {kernel name: (launches, total_ms)} for the launches recorded since prof_enable(True)."""
+    n = lib().moc_prof_read(-1, None, 0, None, None)
+    if n < 0:
+        raise MocError(n, "moc_prof_read")
+    out = {}
+    for i in range(n):
+        buf = C.create_string_buffer(128)
+        cnt, ms = C.c_int32(), C.c_float()
+        _check(lib().moc_prof_read(i, buf, 128, C.byref(cnt), C.byref(ms)), "moc_prof_read")
+        out[buf.value.decode()] = (cnt.value, ms.value)
+    return out

@@ -1,7 +1,10 @@
 // C ABI of libmoc: argument validation, layout tables (stage a), workspace
 // layout, and dispatch to the kernel launchers. No kernel code in this file.
 #include <algorithm>
+#include <atomic>
 #include <cstdio>
+#include <map>
+#include <mutex>
 #include <cstring>
 #include <new>
 #include <string>
@@ -39,9 +42,41 @@ int check_common(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int32_t 
     return MOC_OK;
 }
 
+struct ProfRec { const char *name; hipEvent_t e0, e1; };
+std::mutex g_prof_mu;
+std::vector<ProfRec> g_prof;
+std::vector<hipEvent_t> g_prof_pool;
+std::atomic<bool> g_prof_on{false};
+
+hipEvent_t prof_event() {
+    if (!g_prof_pool.empty()) { hipEvent_t e = g_prof_pool.back(); g_prof_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+
+void prof_clear_locked() {
+    for (auto &r : g_prof) { g_prof_pool.push_back(r.e0); g_prof_pool.push_back(r.e1); }
+    g_prof.clear();
+}
+
 }  // namespace
 
 namespace moc {
+
+bool prof_on() { return g_prof_on.load(std::memory_order_relaxed); }
+
+void prof_begin(const char *name, hipStream_t st) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    ProfRec r{name, prof_event(), prof_event()};
+    (void)hipEventRecord(r.e0, st);
+    g_prof.push_back(r);
+}
+
+void prof_end(hipStream_t st) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_prof.empty()) (void)hipEventRecord(g_prof.back().e1, st);
+}
 
 AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd) {
     AttnWs L{};
@@ -88,6 +123,36 @@ const char *moc_status_string(int s) {
 }
 
 const char *moc_last_error(void) { return g_err.c_str(); }
+
+int moc_prof_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    prof_clear_locked();
+    g_prof_on.store(on != 0);
+    return MOC_OK;
+}
+
+int moc_prof_read(int32_t index, char *name, size_t name_cap, int32_t *launches, float *total_ms) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    // aggregate by kernel name, in order of first appearance
+    std::vector<const char *> order;
+    std::map<std::string, std::pair<int, double>> agg;
+    for (auto &r : g_prof) {
+        hipError_t e = hipEventSynchronize(r.e1);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.e0, r.e1);
+        if (e != hipSuccess) return hip_fail(e, "moc_prof_read");
+        auto it = agg.find(r.name);
+        if (it == agg.end()) { order.push_back(r.name); agg[r.name] = {1, ms}; }
+        else { it->second.first += 1; it->second.second += ms; }
+    }
+    if (index < 0) return (int)order.size();           // number of distinct kernels
+    if (index >= (int)order.size()) return fail(MOC_ERR_SHAPE, "profile index out of range");
+    const auto &a = agg[order[index]];
+    if (name && name_cap) { std::strncpy(name, order[index], name_cap - 1); name[name_cap - 1] = 0; }
+    if (launches) *launches = a.first;
+    if (total_ms) *total_ms = (float)a.second;
+    return MOC_OK;
+}
 
 int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot, const int32_t *window,
                    const int32_t *spans, int32_t T, void *stream, moc_meta **out) {

@@ -50,11 +50,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(FwdArgs a) {
     __shared__ __attribute__((aligned(16))) bf16_t Kt[D * ColTile<BN>::kStride];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
-    const int bh = blockIdx.y;
     const int N = a.N;
 
+    int logical;
+    if (!xcd_remap((long long)a.items_per_head * a.BH, logical)) return;
+    const int bh = logical / a.items_per_head;
     ItemDesc it;
-    if (!decode_item<MODE>(a, bh, blockIdx.x, it)) return;
+    if (!decode_item<MODE>(a, bh, logical - bh * a.items_per_head, it)) return;
 
     const int r = wave * 32 + l32;
     const bool row_valid = r < it.q_count;
@@ -173,7 +175,7 @@ struct KvArgs {
     float *tpart_k, *tpart_v;
     const KvItem *items;
     const int32_t *list_off, *qlist;
-    int N, C, topk, n_partials;
+    int N, C, topk, n_partials, n_items, BH;
     float scale, scale_log2;
 };
 
@@ -188,9 +190,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
     __shared__ float lse_s[BQ], delta_s[BQ];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
-    const int bh = blockIdx.y;
     const int N = a.N;
-    const KvItem item = a.items[blockIdx.x];
+    int logical;
+    if (!xcd_remap((long long)a.n_items * a.BH, logical)) return;
+    const int bh = logical / a.n_items;
+    const KvItem item = a.items[logical - bh * a.n_items];
 
     const T *qbase = static_cast<const T *>(a.q) + (size_t)bh * N * D;
     const T *kbase = static_cast<const T *>(a.k) + (size_t)bh * N * D;
@@ -349,18 +353,25 @@ static hipError_t bwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, KvArgs &kv
                                void *dq, hipStream_t st) {
     constexpr int QPW = 256 / (D / 8);
     const size_t rows = (size_t)BH * m->N;
+    { MOC_PROF("delta", st);
     delta_kernel<D, T><<<dim3((unsigned)((rows + QPW - 1) / QPW)), dim3(256), 0, st>>>(
-        static_cast<const T *>(o), static_cast<const T *>(a.d_o), rows, const_cast<float *>(a.delta));
-    attn_bwd_dkdv_kernel<D, T><<<dim3(m->n_kvitems, BH), dim3(256), 0, st>>>(kv);
-    if (m->n_text_tiles > 0)
+        static_cast<const T *>(o), static_cast<const T *>(a.d_o), rows, const_cast<float *>(a.delta)); }
+    { MOC_PROF("attn_bwd_dkdv", st);
+    attn_bwd_dkdv_kernel<D, T><<<dim3(xcd_grid((long long)m->n_kvitems * BH)), dim3(256), 0, st>>>(kv); }
+    if (m->n_text_tiles > 0) { MOC_PROF("text_reduce", st);
         text_reduce_kernel<D, T><<<dim3(m->n_text_tiles, BH), dim3(256), 0, st>>>(
             kv.tpart_k, kv.tpart_v, m->d_text_tiles, m->n_partials, m->N, static_cast<T *>(kv.dk),
-            static_cast<T *>(kv.dv));
+            static_cast<T *>(kv.dv)); }
+    a.BH = BH;
     if (a.topk > 0) {
-        const int max_tiles = (m->N * a.topk + kBM - 1) / kBM + m->C;
-        attn_bwd_dq_kernel<D, T, MODE_ROUTED><<<dim3(max_tiles, BH), dim3(256), 0, st>>>(a);
+        a.items_per_head = (m->N * a.topk + kBM - 1) / kBM + m->C;
+        MOC_PROF("attn_bwd_dq_routed", st);
+        attn_bwd_dq_kernel<D, T, MODE_ROUTED><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a);
     }
-    attn_bwd_dq_kernel<D, T, MODE_ANCHOR><<<dim3(m->n_atiles, BH), dim3(256), 0, st>>>(a);
+    { MOC_PROF("attn_bwd_dq_forced", st);
+    a.items_per_head = m->n_atiles;
+    attn_bwd_dq_kernel<D, T, MODE_ANCHOR><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a); }
+    MOC_PROF("dq_merge", st);
     dq_merge_kernel<D, T><<<dim3((m->N + QPW - 1) / QPW, BH), dim3(256), 0, st>>>(a.po, sel, m->N, m->C, a.topk,
                                                                                 static_cast<T *>(dq));
     return hipGetLastError();
@@ -390,7 +401,7 @@ hipError_t launch_attn_bwd(const moc_meta *m, int BH, int d, int dtype, const vo
     kv.tpart_v = reinterpret_cast<float *>(ws + L.tpart_v);
     kv.items = m->d_kvitems;
     kv.list_off = a.list_off; kv.qlist = a.qlist;
-    kv.N = m->N; kv.C = m->C; kv.topk = topk; kv.n_partials = m->n_partials;
+    kv.N = m->N; kv.C = m->C; kv.topk = topk; kv.n_partials = m->n_partials; kv.n_items = m->n_kvitems; kv.BH = BH;
     kv.scale = scale; kv.scale_log2 = a.scale_log2;
     if (dtype == MOC_BF16) return d == 128 ? bwd_dispatch<128, bf16_t>(m, BH, a, kv, o, sel, dq, st)
                                            : bwd_dispatch<64, bf16_t>(m, BH, a, kv, o, sel, dq, st);

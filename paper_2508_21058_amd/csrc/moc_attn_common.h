@@ -14,6 +14,7 @@ struct FwdArgs {
     bf16_t *po;        // [BH, N, slots, D] partial outputs (forward) / partial dQ (backward)
     float *plse;       // [BH, N, slots]   partial log-sum-exp (forward only)
     int N, C, topk, slots;
+    int BH, items_per_head;   // work list of the launch: items_per_head entries per (batch, head)
     float scale, scale_log2;
     const AnchorTile *atiles;
     const int32_t *arange_off;
@@ -23,6 +24,19 @@ struct FwdArgs {
     const void *d_o;
     const float *lse, *delta;
 };
+
+// The GPU has 8 XCDs with private L2 caches and hands consecutive workgroups to
+// them round-robin. Work lists are ordered so that neighbours share K/V (or
+// Q/dO), hence XCD x takes the contiguous slice [x*per, (x+1)*per) of the list.
+// Launch ceil(total/8)*8 workgroups on a 1-D grid; returns false for padding.
+constexpr int kXcds = 8;
+__host__ __device__ inline int xcd_grid(long long total) { return (int)((total + kXcds - 1) / kXcds) * kXcds; }
+__device__ __forceinline__ bool xcd_remap(long long total, int &logical) {
+    const int L = blockIdx.x;
+    const int per = (int)((total + kXcds - 1) / kXcds);
+    logical = (L % kXcds) * per + L / kXcds;
+    return logical < total;
+}
 
 struct ItemDesc {
     int q_start, q_count;
@@ -116,6 +130,77 @@ template <int D, typename T, int ROWS> struct RowStager {
                 *reinterpret_cast<u32x4 *>(lds + row * RowTile<D>::kStride + cg * 8) = __builtin_bit_cast(u32x4, reg[p]);
         }
     }
+    // same rows into a swizzled tile (SwTile<D>)
+    __device__ __forceinline__ void store_sw(bf16_t *lds) const {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int row = rr + p * RPP;
+            if (ROWS % RPP == 0 || row < ROWS)
+                *reinterpret_cast<u32x4 *>(lds + SwTile<D>::off(row, cg)) = __builtin_bit_cast(u32x4, reg[p]);
+        }
+    }
+};
+
+// Moves ROWS source rows of D features into a swizzled LDS tile (SwTile<D>).
+//   issue(base, rowfn, lds)  starts the transfer of a tile into `lds`
+//   commit(lds)              finishes it (before the barrier that publishes `lds`)
+// bf16 storage: asynchronous global->LDS loads (global_load_lds_dwordx4): no
+// staging registers, no LDS store instructions. One wave instruction fills 1 KB
+// of LDS, lane l writing bytes [16 l, 16 l + 16), so each lane fetches the
+// global element that belongs at its swizzled LDS position.
+// fp32 storage needs a conversion, so it goes through registers.
+template <int D, typename T, int ROWS> struct TileLoader;
+
+template <int D, int ROWS> struct TileLoader<D, bf16_t, ROWS> {
+    static constexpr int RPI = 512 / D;                 // rows per wave instruction
+    static constexpr int NI = ROWS / RPI;               // wave instructions per tile
+    static constexpr int P = (NI + 3) / 4;              // per wave (4 waves)
+    int wave, rlo, cgp;
+    __device__ __forceinline__ explicit TileLoader(int tid)
+        : wave(__builtin_amdgcn_readfirstlane(tid >> 6)), rlo((tid & 63) / (D / 8)), cgp((tid & 63) % (D / 8)) {}
+    static __device__ __forceinline__ void dma(const bf16_t *g, bf16_t *lds) {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                         (__attribute__((address_space(3))) void *)lds, 16, 0, 0);
+    }
+    // arbitrary (gathered) rows: rowfn(r) is the global row of tile row r
+    template <typename F> __device__ __forceinline__ void issue(const bf16_t *base, F rowfn, bf16_t *lds) const {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int n = wave + 4 * p;
+            if (NI % 4 == 0 || n < NI) {
+                const int row = n * RPI + rlo;
+                const int cg = cgp ^ SwTile<D>::sw(row);
+                dma(base + (size_t)rowfn(row) * D + cg * 8, lds + n * 512);
+            }
+        }
+    }
+    // contiguous rows [0, valid) of a tile whose first row is at `tile` (a
+    // wave-uniform pointer): scalar base + one 32-bit lane offset per load
+    __device__ __forceinline__ void issue_rows(const bf16_t *tile, int valid, bf16_t *lds) const {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int n = wave + 4 * p;
+            if (NI % 4 == 0 || n < NI) {
+                const int row = n * RPI + rlo;
+                const int cg = cgp ^ SwTile<D>::sw(row);
+                const uint32_t off = (uint32_t)(min(row, valid - 1) * D + cg * 8) * 2u;
+                dma(reinterpret_cast<const bf16_t *>(reinterpret_cast<const char *>(tile) + off), lds + n * 512);
+            }
+        }
+    }
+    __device__ __forceinline__ void commit(bf16_t *) const {}
+};
+
+template <int D, int ROWS> struct TileLoader<D, float, ROWS> {
+    RowStager<D, float, ROWS> st;
+    __device__ __forceinline__ explicit TileLoader(int tid) : st(tid) {}
+    template <typename F> __device__ __forceinline__ void issue(const float *base, F rowfn, bf16_t *) {
+        st.load_fn(base, rowfn);
+    }
+    __device__ __forceinline__ void issue_rows(const float *tile, int valid, bf16_t *) {
+        st.load_fn(tile, [=](int r) { return min(r, valid - 1); });
+    }
+    __device__ __forceinline__ void commit(bf16_t *lds) const { st.store_sw(lds); }
 };
 
 // Stages COLS source rows transposed into ColTile<COLS> ([D][COLS+4]): a lane

@@ -8,28 +8,118 @@
 // slot of the (query, link) pair; a merge kernel combines the <= topk+1 partials
 // of a query (the usual split-softmax identity), so no item ever waits on another.
 //
-// Per workgroup: 4 waves x 32 query rows. K tiles (64 keys) are staged row-major
-// and V tiles transposed in LDS; S^T = K Q^T and O^T = V^T P^T are computed so
-// that each lane owns one query column: softmax statistics are per-lane scalars
-// and the S^T accumulator feeds the second product without any shuffle.
+// Per workgroup: 4 waves x 32 query rows. K and V tiles (64 keys) are staged
+// row-major in swizzled LDS tiles; V is read back through the transposing LDS
+// load. S^T = K Q^T and O^T = V^T P^T are computed so that each lane owns one
+// query column: softmax statistics are per-lane scalars and the S^T accumulator
+// feeds the second product without any shuffle.
 #include "moc_attn_common.h"
 
 namespace moc {
+
+// One tile (BN = 64 keys) of the online-softmax recurrence for this wave's 32
+// queries. Rows >= valid of a ragged tile hold copies of the last valid key and
+// are masked to -inf. LDS reads are pinned a few fragments ahead of the matrix
+// instructions that consume them.
+template <int D>
+__device__ __forceinline__ void fwd_tile(const bf16_t *Ks, const bf16_t *Vs, const bf16x8 *qf, f32x16 *oacc,
+                                         float &m_run, float &l_run, float c, int valid, int lane) {
+    constexpr int KS = D / 16, DB = D / 32;
+    const int half = lane >> 5, l32 = lane & 31;
+    f32x16 sacc[2];
+    {
+        bf16x8 kf[2 * KS];
+#pragma unroll
+        for (int u = 0; u < 2 * KS; ++u) kf[u] = SwTile<D>::frag(Ks, (u / KS) * 32 + l32, u % KS, half);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            sacc[kb] = mfma32(kf[kb * KS], qf[0], zero16());
+#pragma unroll
+            for (int s = 1; s < KS; ++s) sacc[kb] = mfma32(kf[kb * KS + s], qf[s], sacc[kb]);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int u = 0; u < 2 * KS - 4; ++u) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
+    if (valid < 64) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int key = kb * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
+                if (key >= valid) sacc[kb][i] = -INFINITY;
+            }
+    }
+    // online softmax over this lane's 32 keys, then across the two halves
+    float mx = sacc[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
+    mx = fmaxf(mx, xhalf(mx));
+    const float m_new = fmaxf(m_run, mx);
+    if (__any(m_new > m_run)) {
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        l_run *= alpha;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+        m_run = m_new;
+    }
+    const float mc = m_run * c;
+    float ls = 0.f;
+    // O^T[feature][query] += V^T P^T, 16 keys at a time; V is read transposed
+    // straight from its row-major tile
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 vf[DB];
+#pragma unroll
+        for (int b = 0; b < DB; ++b) vf[b] = SwTile<D>::tfrag(Vs, lane, b, ks);
+        f32x16 &sa = sacc[ks >> 1];
+#pragma unroll
+        for (int i = 8 * (ks & 1); i < 8 * (ks & 1) + 8; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(sa[i], c, -mc));
+            sa[i] = p;
+            ls += p;
+        }
+        const bf16x8 pf = acc_to_frag(sa, ks & 1);
+#pragma unroll
+        for (int b = 0; b < DB; ++b) oacc[b] = mfma32(vf[b], pf, oacc[b]);
+    }
+    l_run += ls;
+    // 2*DB transposing reads per 16-key step; keep one step of reads in flight
+    __builtin_amdgcn_sched_group_barrier(0x100, 4 * DB, 0);
+#pragma unroll
+    for (int u = 0; u < 2 * DB; ++u) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * DB, 0);
+}
 
 template <int D, typename T, int MODE>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
     constexpr int BN = 64;
     constexpr int KS = D / 16;   // feature steps of the QK product
     constexpr int DB = D / 32;   // 32-feature blocks of the output
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[BN * RowTile<D>::kStride];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[D * ColTile<BN>::kStride];
+    __shared__ __attribute__((aligned(1024))) bf16_t K0[BN * D];
+    __shared__ __attribute__((aligned(1024))) bf16_t K1[BN * D];
+    __shared__ __attribute__((aligned(1024))) bf16_t V0[BN * D];
+    __shared__ __attribute__((aligned(1024))) bf16_t V1[BN * D];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
-    const int bh = blockIdx.y;
     const int N = a.N;
 
+    int logical;
+    if (!xcd_remap((long long)a.items_per_head * a.BH, logical)) return;
+    const int bh = logical / a.items_per_head;
     ItemDesc it;
-    if (!decode_item<MODE>(a, bh, blockIdx.x, it)) return;
+    if (!decode_item<MODE>(a, bh, logical - bh * a.items_per_head, it)) return;
 
     // ---- this lane's query row
     const int r = wave * 32 + l32;
@@ -54,83 +144,33 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
     float m_run = -INFINITY, l_run = 0.f;
     const float c = a.scale_log2;
 
-    RowStager<D, T, BN> kst(tid);
-    ColStager<D, T, BN> vst(tid);
+    // Double-buffered pipeline, one barrier per tile: while tile t is consumed
+    // from one LDS buffer, tile t+1 streams from global memory into the other.
+    // The loop is unrolled by two so every access names a fixed buffer.
+    TileLoader<D, T, BN> kld(tid), vld(tid);
     TileIter<BN> ti(it);
-    kst.load(kbase, ti.start(), ti.valid());
-    vst.load(vbase, ti.start(), ti.valid());
+    int valid = ti.valid();
+    bool more;
+    auto issue = [&](bf16_t *Kn, bf16_t *Vn) {
+        const size_t st = (size_t)ti.start() * D;
+        kld.issue_rows(kbase + st, ti.valid(), Kn);
+        vld.issue_rows(vbase + st, ti.valid(), Vn);
+    };
+    auto stage = [&](const bf16_t *Kc, const bf16_t *Vc, bf16_t *Kn, bf16_t *Vn) {
+        const int cur_valid = valid;
+        more = ti.next();
+        if (more) { valid = ti.valid(); issue(Kn, Vn); }
+        if (wave_active) fwd_tile<D>(Kc, Vc, qf, oacc, m_run, l_run, c, cur_valid, lane);
+        if (more) { kld.commit(Kn); vld.commit(Vn); __syncthreads(); }
+        return more;       // false: Kc/Vc held the last tile
+    };
+    issue(K0, V0);
+    kld.commit(K0);
+    vld.commit(V0);
+    __syncthreads();
     while (true) {
-        __syncthreads();
-        kst.store(Ks);
-        vst.store(Vt);
-        __syncthreads();
-        const int valid = ti.valid();
-        const bool more = ti.next();
-        if (more) {
-            kst.load(kbase, ti.start(), ti.valid());
-            vst.load(vbase, ti.start(), ti.valid());
-        }
-        if (wave_active) {
-            // S^T[key][query]
-            f32x16 sacc[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                sacc[kb] = zero16();
-                if (kb * 32 < valid) {
-#pragma unroll
-                    for (int s = 0; s < KS; ++s)
-                        sacc[kb] = mfma32(RowTile<D>::frag(Ks, kb * 32 + l32, s, half), qf[s], sacc[kb]);
-                }
-            }
-            if (valid < BN) {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int key = kb * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
-                        if (key >= valid) sacc[kb][i] = -INFINITY;
-                    }
-            }
-            // online softmax over this lane's 32 keys, then across the two halves
-            float mx = sacc[0][0];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
-            mx = fmaxf(mx, xhalf(mx));
-            const float m_new = fmaxf(m_run, mx);
-            if (__any(m_new > m_run)) {
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-                l_run *= alpha;
-#pragma unroll
-                for (int b = 0; b < DB; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
-                m_run = m_new;
-            }
-            const float mc = m_run * c;
-            float ls = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], c, -mc));
-                    sacc[kb][i] = p;
-                    ls += p;
-                }
-            l_run += ls;
-            // O^T[feature][query] += V^T P^T
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                if (ks * 16 < valid) {
-                    const bf16x8 pf = acc_to_frag(sacc[ks >> 1], ks & 1);
-#pragma unroll
-                    for (int b = 0; b < DB; ++b)
-                        oacc[b] = mfma32(ColTile<BN>::frag(Vt, b * 32 + l32, ks, half), pf, oacc[b]);
-                }
-            }
-        }
-        if (!more) break;
+        if (!stage(K0, V0, K1, V1)) break;
+        if (!stage(K1, V1, K0, V0)) break;
     }
 
     if (!row_valid) return;
@@ -198,11 +238,16 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(const bf16_t *__restrict
 template <int D, typename T>
 static hipError_t fwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, const int32_t *sel, void *o, float *lse,
                                hipStream_t st) {
+    a.BH = BH;
     if (a.topk > 0) {
-        const int max_tiles = (m->N * a.topk + kBM - 1) / kBM + m->C;
-        attn_fwd_kernel<D, T, MODE_ROUTED><<<dim3(max_tiles, BH), dim3(256), 0, st>>>(a);
+        a.items_per_head = (m->N * a.topk + kBM - 1) / kBM + m->C;   // upper bound; surplus items exit at once
+        MOC_PROF("attn_fwd_routed", st);
+        attn_fwd_kernel<D, T, MODE_ROUTED><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a);
     }
-    attn_fwd_kernel<D, T, MODE_ANCHOR><<<dim3(m->n_atiles, BH), dim3(256), 0, st>>>(a);
+    { MOC_PROF("attn_fwd_forced", st);
+    a.items_per_head = m->n_atiles;
+    attn_fwd_kernel<D, T, MODE_ANCHOR><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a); }
+    MOC_PROF("fwd_merge", st);
     constexpr int QPW = 256 / (D / 8);
     fwd_merge_kernel<D, T><<<dim3((m->N + QPW - 1) / QPW, BH), dim3(256), 0, st>>>(
         a.po, a.plse, sel, m->N, m->C, a.topk, static_cast<T *>(o), lse);

@@ -134,4 +134,41 @@ template <int COLS> struct ColTile {
     }
 };
 
+// Row-major LDS tile [ROWS][D] of bf16 without padding; the 16-byte column
+// groups of a row are XOR-swizzled by the row index so that BOTH access
+// patterns below are bank-conflict free:
+//   frag()   row operand: 16 consecutive rows read the same 16-byte group;
+//   tfrag()  transposed operand through ds_read_b64_tr_b16: a 32-lane phase
+//            reads a patch of 4 rows x 32 features.
+// ds_read_b64_tr_b16 (gfx950): within each block of 16 lanes, lane i receives
+// element (i & 3) of the 8-byte words addressed by lanes (i >> 2) + {0,4,8,12}.
+// With lane j of a block pointing at (row R0 + j/4, features F0 + 4*(j%4) ..+4)
+// lane i ends up with feature F0 + i of rows R0 .. R0+3: a 4 x 16 patch, transposed.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+template <int D> struct SwTile {
+    static constexpr int CG = D / 8;
+    static __device__ __forceinline__ int sw(int row) { return (((row & 3) << 2) | ((row >> 2) & 3)) & (CG - 1); }
+    static __device__ __forceinline__ int off(int row, int cg) { return row * D + ((cg ^ sw(row)) << 3); }
+    // row operand: row r, features [16*step + 8*half, +8)
+    static __device__ __forceinline__ bf16x8 frag(const bf16_t *base, int r, int step, int half) {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + off(r, 2 * step + half)));
+    }
+    // transposed operand for the lane's feature 32*db + (lane & 31): contraction
+    // slots 0..3 -> rows 16*s + 4*half + {0..3}, slots 4..7 -> the same + 8
+    // (the slot order of acc_to_frag).
+    static __device__ __forceinline__ bf16x8 tfrag(const bf16_t *base, int lane, int db, int s) {
+        const int i = lane & 15, bq = (lane >> 4) & 1, half = lane >> 5;
+        const int x = 32 * db + 16 * bq + 4 * (i & 3);
+        const int r0 = 16 * s + 4 * half + (i >> 2);
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        const bf16_t *p0 = base + off(r0, x >> 3) + (x & 7);
+        const bf16_t *p1 = base + off(r0 + 8, x >> 3) + (x & 7);
+        s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p0);
+        s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p1);
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+        return __builtin_bit_cast(bf16x8, r);
+    }
+};
+
 }  // namespace moc

@@ -54,6 +54,19 @@ struct moc_meta {
 
 namespace moc {
 
+// Optional per-kernel timing with HIP events on the launch stream (off by
+// default; switched on through moc_prof_enable). A Scope brackets one launch.
+bool prof_on();
+void prof_begin(const char *name, hipStream_t st);
+void prof_end(hipStream_t st);
+struct ProfScope {
+    hipStream_t st;
+    bool on;
+    ProfScope(const char *name, hipStream_t s) : st(s), on(prof_on()) { if (on) prof_begin(name, s); }
+    ~ProfScope() { if (on) prof_end(st); }
+};
+#define MOC_PROF(name, st) ::moc::ProfScope moc_prof_scope_(name, st)
+
 // Layout of the attention workspace (byte offsets); shared by fwd and bwd.
 struct AttnWs {
     size_t cnt, list_off, tile_off, cursor, qlist, plse, po, delta, tpart_k, tpart_v, total;

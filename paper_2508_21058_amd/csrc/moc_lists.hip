@@ -146,6 +146,7 @@ hipError_t launch_build_lists(const moc_meta *m, int BH, int topk, const int32_t
     // cnt and cursor are adjacent sections; clear both (a fill kernel, so the
     // call can be captured into a graph)
     const size_t nz = (size_t)BH * C;
+    MOC_PROF("build_lists", st);
     zero_i32_kernel<<<dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st>>>(cnt, nz);
     zero_i32_kernel<<<dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st>>>(cursor, nz);
     dim3 grid((NK + kEntPerWg - 1) / kEntPerWg, BH), block(256);

@@ -86,6 +86,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ k, cons
 
 hipError_t launch_pool(const moc_meta *m, int BH, int d, int dtype, const void *k, float *kbar, hipStream_t st) {
     dim3 grid(m->C, BH), block(256);
+    MOC_PROF("pool", st);
 #define MOC_POOL(DD, TT) \
     pool_kernel<DD, TT><<<grid, block, 0, st>>>(static_cast<const TT *>(k), m->d_off, m->N, m->C, kbar)
     if (dtype == MOC_BF16) { if (d == 128) MOC_POOL(128, bf16_t); else MOC_POOL(64, bf16_t); }

@@ -94,6 +94,7 @@ __global__ __launch_bounds__(256) void route_kernel(const T *__restrict__ q, con
 hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void *q, const float *kbar, int topk,
                         int causal, int32_t *sel, hipStream_t st) {
     dim3 grid((m->N + 255) / 256, BH), block(256);
+    MOC_PROF("route_topk", st);
 #define MOC_ROUTE(DD, TT, KK)                                                                              \
     route_kernel<DD, TT, KK><<<grid, block, 0, st>>>(static_cast<const TT *>(q), kbar, m->d_chunk_of, m->d_kind, \
                                                      m->d_win, m->d_wfirst, m->d_wlast, m->N, m->C, topk,  \
