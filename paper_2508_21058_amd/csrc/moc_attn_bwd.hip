@@ -41,13 +41,69 @@ __global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ o, con
 }
 
 // ------------------------------------------------------------------ dQ pass
+// 32 keys (rows ROW0 .. ROW0+31 of the staged 64-key tiles at byte offsets KOFF
+// and VOFF) against this wave's 32 queries: S^T and dP^T from row reads of K
+// and V, dS^T, then dQ^T[feature][query] += K^T dS^T with K read transposed
+// from the same tile.
+template <int D, int KOFF, int VOFF, int ROW0>
+__device__ __forceinline__ void dq_half_tile(const char *smem, LaneOffs<D> &lo, const bf16x8 *qf, const bf16x8 *dof,
+                                             f32x16 *dqacc, float c, float lse2, float dl, int valid, int lane) {
+    constexpr int KS = D / 16, DB = D / 32;
+    constexpr int RB = ROW0 * D * 2;
+    const int half = lane >> 5;
+    lo.pin();
+    f32x16 sacc, dpacc;
+    {
+        bf16x8 kf[KS], vf[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kf[s] = lo.template frag<KOFF + RB>(smem, s);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) vf[s] = lo.template frag<VOFF + RB>(smem, s);
+        sacc = mfma32(kf[0], qf[0], zero16());
+#pragma unroll
+        for (int s = 1; s < KS; ++s) sacc = mfma32(kf[s], qf[s], sacc);
+        dpacc = mfma32(vf[0], dof[0], zero16());
+#pragma unroll
+        for (int s = 1; s < KS; ++s) dpacc = mfma32(vf[s], dof[s], dpacc);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int u = 0; u < 2 * KS - 4; ++u) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int key = ROW0 + (i >> 2) * 8 + half * 4 + (i & 3);
+        float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, -lse2));
+        if (key >= valid) p = 0.f;
+        sacc[i] = p * (dpacc[i] - dl);
+    }
+    {
+        bf16x8 ktf[DB];
+#pragma unroll
+        for (int b = 0; b < DB; ++b) ktf[b] = lo.template tfrag<KOFF + RB>(smem, b);
+        const bf16x8 dsf = acc_to_frag(sacc, 0);
+#pragma unroll
+        for (int b = 0; b < DB; ++b) dqacc[b] = mfma32(ktf[b], dsf, dqacc[b]);
+    }
+    {
+        bf16x8 ktf[DB];
+#pragma unroll
+        for (int b = 0; b < DB; ++b) ktf[b] = lo.template tfrag<KOFF + RB + 16 * D * 2>(smem, b);
+        const bf16x8 dsf = acc_to_frag(sacc, 1);
+#pragma unroll
+        for (int b = 0; b < DB; ++b) dqacc[b] = mfma32(ktf[b], dsf, dqacc[b]);
+    }
+}
+
 template <int D, typename T, int MODE>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(FwdArgs a) {
-    constexpr int BN = 32;
+    constexpr int BN = 64;
     constexpr int KS = D / 16, DB = D / 32;
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[BN * RowTile<D>::kStride];
-    __shared__ __attribute__((aligned(16))) bf16_t Vs[BN * RowTile<D>::kStride];
-    __shared__ __attribute__((aligned(16))) bf16_t Kt[D * ColTile<BN>::kStride];
+    constexpr int TB = BN * D * 2;
+    __shared__ __attribute__((aligned(1024))) char smem[4 * TB];   // K0 K1 V0 V1
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
     const int N = a.N;
@@ -64,7 +120,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(FwdArgs a) {
     const int rc = row_valid ? r : it.q_count - 1;
     int qi, slot;
     if (MODE == MODE_ANCHOR) { qi = it.q_start + rc; slot = a.topk; }
-    else { const int e = it.entries[rc]; qi = e / a.topk; slot = e - qi * a.topk; }
+    else { const int e = it.entries[rc]; qi = e >> 5; slot = e & 31; }
 
     const T *qbase = static_cast<const T *>(a.q) + (size_t)bh * N * D;
     const T *kbase = static_cast<const T *>(a.k) + (size_t)bh * N * D;
@@ -84,51 +140,43 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(FwdArgs a) {
     f32x16 dqacc[DB];
 #pragma unroll
     for (int b = 0; b < DB; ++b) dqacc[b] = zero16();
+    LaneOffs<D> lo;
+    lo.init(lane);
 
-    RowStager<D, T, BN> kst(tid), vst(tid);
-    ColStager<D, T, BN> ktst(tid);
+    TileLoader<D, T, BN> kld(tid), vld(tid);
     TileIter<BN> ti(it);
-    kst.load(kbase, ti.start(), ti.valid());
-    vst.load(vbase, ti.start(), ti.valid());
-    ktst.load(kbase, ti.start(), ti.valid());
-    while (true) {
-        __syncthreads();
-        kst.store(Ks);
-        vst.store(Vs);
-        ktst.store(Kt);
-        __syncthreads();
-        const int valid = ti.valid();
-        const bool more = ti.next();
-        if (more) {
-            kst.load(kbase, ti.start(), ti.valid());
-            vst.load(vbase, ti.start(), ti.valid());
-            ktst.load(kbase, ti.start(), ti.valid());
-        }
+    int valid = ti.valid();
+    bool more;
+    auto issue = [&](int buf) {
+        const size_t st = (size_t)ti.start() * D;
+        kld.issue_rows(kbase + st, ti.valid(), reinterpret_cast<bf16_t *>(smem + buf * TB));
+        vld.issue_rows(vbase + st, ti.valid(), reinterpret_cast<bf16_t *>(smem + (2 + buf) * TB));
+    };
+    auto commit = [&](int buf) {
+        kld.commit(reinterpret_cast<bf16_t *>(smem + buf * TB));
+        vld.commit(reinterpret_cast<bf16_t *>(smem + (2 + buf) * TB));
+    };
+    auto stage = [&](auto cur) {
+        constexpr int CUR = decltype(cur)::value;
+        const int cur_valid = valid;
+        more = ti.next();
+        if (more) { valid = ti.valid(); issue(CUR ^ 1); }
         if (wave_active) {
-            f32x16 sacc = zero16(), dpacc = zero16();
-#pragma unroll
-            for (int s = 0; s < KS; ++s) sacc = mfma32(RowTile<D>::frag(Ks, l32, s, half), qf[s], sacc);
-#pragma unroll
-            for (int s = 0; s < KS; ++s) dpacc = mfma32(RowTile<D>::frag(Vs, l32, s, half), dof[s], dpacc);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int key = (i >> 2) * 8 + half * 4 + (i & 3);
-                float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, -lse2));
-                if (key >= valid) p = 0.f;
-                sacc[i] = p * (dpacc[i] - dl);
-            }
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                if (ks * 16 < valid) {
-                    const bf16x8 dsf = acc_to_frag(sacc, ks);
-#pragma unroll
-                    for (int b = 0; b < DB; ++b)
-                        dqacc[b] = mfma32(ColTile<BN>::frag(Kt, b * 32 + l32, ks, half), dsf, dqacc[b]);
-                }
-            }
+            dq_half_tile<D, CUR * TB, (2 + CUR) * TB, 0>(smem, lo, qf, dof, dqacc, c, lse2, dl, cur_valid, lane);
+            if (cur_valid > 32)
+                dq_half_tile<D, CUR * TB, (2 + CUR) * TB, 32>(smem, lo, qf, dof, dqacc, c, lse2, dl, cur_valid, lane);
         }
-        if (!more) break;
+        if (more) { commit(CUR ^ 1); __syncthreads(); }
+        return more;
+    };
+    issue(0);
+    commit(0);
+    __syncthreads();
+    while (true) {
+        if (!stage(IC<0>{})) break;
+        if (!stage(IC<1>{})) break;
     }
+
     if (!row_valid) return;
     bf16_t *po = a.po + (((size_t)bh * N + qi) * a.slots + slot) * D;
     const float sc = a.scale;
@@ -179,15 +227,78 @@ struct KvArgs {
     float scale, scale_log2;
 };
 
+// One block of 32 queries (rows ROW0.. of the staged 64-query Q and dO tiles at
+// byte offsets QOFF / DOOFF) against this wave's 32 keys:
+//   S = Q K^T, dP = dO V^T (row reads of Q, dO; K, V fragments in registers)
+//   P, dS (lane owns a key column, registers run over query rows)
+//   dV^T += dO^T P, dK^T += Q^T dS (Q, dO read transposed from the same tiles)
+template <int D, int QOFF, int DOOFF, int ROW0>
+__device__ __forceinline__ void dkdv_block(const char *smem, LaneOffs<D> &lo, const float *lse_s, const float *delta_s,
+                                           const bf16x8 *kf, const bf16x8 *vf, f32x16 *dkacc, f32x16 *dvacc,
+                                           float c, int nv, int lane) {
+    constexpr int KS = D / 16, DB = D / 32;
+    constexpr int RB = ROW0 * D * 2;
+    const int half = lane >> 5;
+    lo.pin();
+    f32x16 sacc, dpacc;
+    {
+        bf16x8 qa[KS], da[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qa[s] = lo.template frag<QOFF + RB>(smem, s);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) da[s] = lo.template frag<DOOFF + RB>(smem, s);
+        sacc = mfma32(qa[0], kf[0], zero16());
+#pragma unroll
+        for (int s = 1; s < KS; ++s) sacc = mfma32(qa[s], kf[s], sacc);
+        dpacc = mfma32(da[0], vf[0], zero16());
+#pragma unroll
+        for (int s = 1; s < KS; ++s) dpacc = mfma32(da[s], vf[s], dpacc);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int u = 0; u < 2 * KS - 4; ++u) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int row = ROW0 + g * 8 + half * 4;
+        const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + row);
+        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(delta_s + row);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = 4 * g + e;
+            float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, -l4[e]));
+            if (row + e >= nv) p = 0.f;
+            sacc[i] = p;
+            dpacc[i] = p * (dpacc[i] - d4[e]);
+        }
+    }
+#define MOC_KV_STEP(KSTEP)                                                                                   \
+    {                                                                                                        \
+        bf16x8 dot[DB], qt[DB];                                                                              \
+        _Pragma("unroll") for (int b = 0; b < DB; ++b)                                                       \
+            dot[b] = lo.template tfrag<DOOFF + RB + (KSTEP) * 16 * D * 2>(smem, b);                          \
+        _Pragma("unroll") for (int b = 0; b < DB; ++b)                                                       \
+            qt[b] = lo.template tfrag<QOFF + RB + (KSTEP) * 16 * D * 2>(smem, b);                            \
+        const bf16x8 pf = acc_to_frag(sacc, KSTEP);                                                          \
+        const bf16x8 dsf = acc_to_frag(dpacc, KSTEP);                                                        \
+        _Pragma("unroll") for (int b = 0; b < DB; ++b) dvacc[b] = mfma32(dot[b], pf, dvacc[b]);              \
+        _Pragma("unroll") for (int b = 0; b < DB; ++b) dkacc[b] = mfma32(qt[b], dsf, dkacc[b]);              \
+    }
+    MOC_KV_STEP(0) MOC_KV_STEP(1)
+#undef MOC_KV_STEP
+}
+
 template <int D, typename T>
 __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
-    constexpr int BQ = 32;
+    constexpr int BQ = 64;
     constexpr int KS = D / 16, DB = D / 32;
-    __shared__ __attribute__((aligned(16))) bf16_t Qs[BQ * RowTile<D>::kStride];
-    __shared__ __attribute__((aligned(16))) bf16_t dOs[BQ * RowTile<D>::kStride];
-    __shared__ __attribute__((aligned(16))) bf16_t Qt[D * ColTile<BQ>::kStride];
-    __shared__ __attribute__((aligned(16))) bf16_t dOt[D * ColTile<BQ>::kStride];
-    __shared__ float lse_s[BQ], delta_s[BQ];
+    constexpr int TB = BQ * D * 2;
+    // LDS: Q buffers at 0 and TB, dO buffers at 2 TB and 3 TB
+    __shared__ __attribute__((aligned(1024))) char smem[4 * TB];
+    __shared__ __attribute__((aligned(16))) float lse_s[2][BQ], delta_s[2][BQ];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
     const int N = a.N;
@@ -216,6 +327,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
     f32x16 dkacc[DB], dvacc[DB];
 #pragma unroll
     for (int b = 0; b < DB; ++b) { dkacc[b] = zero16(); dvacc[b] = zero16(); }
+    LaneOffs<D> lo;
+    lo.init(lane);
 
     // query sources: a contiguous range, then (video chunks) the chunk's routed list
     const int nA = (item.q_len + BQ - 1) / BQ;
@@ -227,73 +340,55 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
         entries = a.qlist + (size_t)bh * N * a.topk + loff[item.chunk];
     }
     const int ntiles = nA + (cntB + BQ - 1) / BQ;
-    const int topk = a.topk;
+    if (ntiles == 0) return;
 
-    RowStager<D, T, BQ> qst(tid), dost(tid);
-    ColStager<D, T, BQ> cst(lane, wave & 1);      // waves 0,1: Q^T   waves 2,3: dO^T
-    const T *cbase = wave < 2 ? qbase : dobase;
-    bf16_t *clds = wave < 2 ? Qt : dOt;
+    TileLoader<D, T, BQ> qld(tid), dold(tid);
     float lreg = 0.f, dreg = 0.f;
-
     auto tile_valid = [&](int t) { return t < nA ? min(BQ, item.q_len - t * BQ) : min(BQ, cntB - (t - nA) * BQ); };
-    auto load_tile = [&](int t) {
+    auto issue = [&](int t, int buf) {
         const int nv = tile_valid(t);
+        bf16_t *qdst = reinterpret_cast<bf16_t *>(smem + buf * TB);
+        bf16_t *dodst = reinterpret_cast<bf16_t *>(smem + (2 + buf) * TB);
         if (t < nA) {
             const int q0 = item.q_start + t * BQ;
-            auto fn = [=](int r) { return q0 + min(r, nv - 1); };
-            qst.load_fn(qbase, fn);
-            dost.load_fn(dobase, fn);
-            cst.load_fn(cbase, fn);
-            if (tid < BQ) { const int i = fn(tid); lreg = lse[i]; dreg = delta[i]; }
+            qld.issue_rows(qbase + (size_t)q0 * D, nv, qdst);
+            dold.issue_rows(dobase + (size_t)q0 * D, nv, dodst);
+            if (tid < BQ) { const int i = q0 + min(tid, nv - 1); lreg = lse[i] * kLog2e; dreg = delta[i]; }
         } else {
             const int32_t *en = entries + (t - nA) * BQ;
-            auto fn = [=](int r) { return en[min(r, nv - 1)] / topk; };
-            qst.load_fn(qbase, fn);
-            dost.load_fn(dobase, fn);
-            cst.load_fn(cbase, fn);
-            if (tid < BQ) { const int i = fn(tid); lreg = lse[i]; dreg = delta[i]; }
+            auto fn = [=](int r) { return en[min(r, nv - 1)] >> 5; };
+            qld.issue(qbase, fn, qdst);
+            dold.issue(dobase, fn, dodst);
+            if (tid < BQ) { const int i = fn(tid); lreg = lse[i] * kLog2e; dreg = delta[i]; }
         }
     };
-
+    auto commit = [&](int buf) {
+        qld.commit(reinterpret_cast<bf16_t *>(smem + buf * TB));
+        dold.commit(reinterpret_cast<bf16_t *>(smem + (2 + buf) * TB));
+        if (tid < BQ) { lse_s[buf][tid] = lreg; delta_s[buf][tid] = dreg; }
+    };
     const float c = a.scale_log2;
-    if (ntiles > 0) load_tile(0);
-    for (int t = 0; t < ntiles; ++t) {
-        __syncthreads();
-        qst.store(Qs);
-        dost.store(dOs);
-        cst.store(clds);
-        if (tid < BQ) { lse_s[tid] = lreg * kLog2e; delta_s[tid] = dreg; }
-        __syncthreads();
+    int t = 0;
+    auto stage = [&](auto cur) {
+        constexpr int CUR = decltype(cur)::value;
         const int nv = tile_valid(t);
-        if (t + 1 < ntiles) load_tile(t + 1);
+        const bool more = t + 1 < ntiles;
+        if (more) issue(t + 1, CUR ^ 1);
         if (wave_active) {
-            // S[query][key], dP[query][key]: lane owns a key column
-            f32x16 sacc = zero16(), dpacc = zero16();
-#pragma unroll
-            for (int s = 0; s < KS; ++s) sacc = mfma32(RowTile<D>::frag(Qs, l32, s, half), kf[s], sacc);
-#pragma unroll
-            for (int s = 0; s < KS; ++s) dpacc = mfma32(RowTile<D>::frag(dOs, l32, s, half), vf[s], dpacc);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = (i >> 2) * 8 + half * 4 + (i & 3);
-                float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, -lse_s[row]));
-                if (row >= nv) p = 0.f;
-                sacc[i] = p;
-                dpacc[i] = p * (dpacc[i] - delta_s[row]);
-            }
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                if (ks * 16 < nv) {
-                    const bf16x8 pf = acc_to_frag(sacc, ks);
-                    const bf16x8 dsf = acc_to_frag(dpacc, ks);
-#pragma unroll
-                    for (int b = 0; b < DB; ++b) {
-                        dvacc[b] = mfma32(ColTile<BQ>::frag(dOt, b * 32 + l32, ks, half), pf, dvacc[b]);
-                        dkacc[b] = mfma32(ColTile<BQ>::frag(Qt, b * 32 + l32, ks, half), dsf, dkacc[b]);
-                    }
-                }
-            }
+            dkdv_block<D, CUR * TB, (2 + CUR) * TB, 0>(smem, lo, lse_s[CUR], delta_s[CUR], kf, vf, dkacc, dvacc, c, nv, lane);
+            if (nv > 32)
+                dkdv_block<D, CUR * TB, (2 + CUR) * TB, 32>(smem, lo, lse_s[CUR], delta_s[CUR], kf, vf, dkacc, dvacc, c, nv, lane);
         }
+        if (more) { commit(CUR ^ 1); __syncthreads(); }
+        ++t;
+        return more;
+    };
+    issue(0, 0);
+    commit(0);
+    __syncthreads();
+    while (true) {
+        if (!stage(IC<0>{})) break;
+        if (!stage(IC<1>{})) break;
     }
 
     if (!wave_active || l32 >= nk) return;

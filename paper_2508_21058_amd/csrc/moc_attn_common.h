@@ -5,6 +5,9 @@
 
 namespace moc {
 
+// compile-time integer tag (selects an LDS buffer in the unrolled pipelines)
+template <int V> struct IC { static constexpr int value = V; };
+
 constexpr int MODE_ANCHOR = 0;  // forced links: window query tile x (text spans + window)
 constexpr int MODE_ROUTED = 1;  // routed links: gathered queries of a chunk x that chunk
 
@@ -40,7 +43,7 @@ __device__ __forceinline__ bool xcd_remap(long long total, int &logical) {
 
 struct ItemDesc {
     int q_start, q_count;
-    const int32_t *entries;   // gathered rows (flat sel indices) or nullptr
+    const int32_t *entries;   // gathered rows ((query << 5) | slot) or nullptr
     int nranges;
     const KeyRange *ranges;   // nullptr: use `single`
     KeyRange single;

@@ -18,19 +18,23 @@
 namespace moc {
 
 // One tile (BN = 64 keys) of the online-softmax recurrence for this wave's 32
-// queries. Rows >= valid of a ragged tile hold copies of the last valid key and
-// are masked to -inf. LDS reads are pinned a few fragments ahead of the matrix
-// instructions that consume them.
-template <int D>
-__device__ __forceinline__ void fwd_tile(const bf16_t *Ks, const bf16_t *Vs, const bf16x8 *qf, f32x16 *oacc,
+// queries; the K tile sits at byte offset KOFF of the workgroup's LDS, the V
+// tile at VOFF. Rows >= valid of a ragged tile hold copies of the last valid key
+// and are masked to -inf. LDS reads are pinned a few fragments ahead of the
+// matrix instructions that consume them.
+template <int D, int KOFF, int VOFF>
+__device__ __forceinline__ void fwd_tile(const char *smem, LaneOffs<D> &lo, const bf16x8 *qf, f32x16 *oacc,
                                          float &m_run, float &l_run, float c, int valid, int lane) {
     constexpr int KS = D / 16, DB = D / 32;
-    const int half = lane >> 5, l32 = lane & 31;
+    const int half = lane >> 5;
+    lo.pin();
     f32x16 sacc[2];
     {
         bf16x8 kf[2 * KS];
 #pragma unroll
-        for (int u = 0; u < 2 * KS; ++u) kf[u] = SwTile<D>::frag(Ks, (u / KS) * 32 + l32, u % KS, half);
+        for (int s = 0; s < KS; ++s) kf[s] = lo.template frag<KOFF>(smem, s);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kf[KS + s] = lo.template frag<KOFF + 32 * D * 2>(smem, s);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             sacc[kb] = mfma32(kf[kb * KS], qf[0], zero16());
@@ -60,8 +64,7 @@ __device__ __forceinline__ void fwd_tile(const bf16_t *Ks, const bf16_t *Vs, con
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
-    mx = fmaxf(mx, xhalf(mx));
-    const float m_new = fmaxf(m_run, mx);
+    const float m_new = fmaxf(m_run, xhalf_max(mx));
     if (__any(m_new > m_run)) {
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
         l_run *= alpha;
@@ -75,22 +78,22 @@ __device__ __forceinline__ void fwd_tile(const bf16_t *Ks, const bf16_t *Vs, con
     float ls = 0.f;
     // O^T[feature][query] += V^T P^T, 16 keys at a time; V is read transposed
     // straight from its row-major tile
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        bf16x8 vf[DB];
-#pragma unroll
-        for (int b = 0; b < DB; ++b) vf[b] = SwTile<D>::tfrag(Vs, lane, b, ks);
-        f32x16 &sa = sacc[ks >> 1];
-#pragma unroll
-        for (int i = 8 * (ks & 1); i < 8 * (ks & 1) + 8; ++i) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(sa[i], c, -mc));
-            sa[i] = p;
-            ls += p;
-        }
-        const bf16x8 pf = acc_to_frag(sa, ks & 1);
-#pragma unroll
-        for (int b = 0; b < DB; ++b) oacc[b] = mfma32(vf[b], pf, oacc[b]);
+#define MOC_PV_STEP(KSTEP)                                                                         \
+    {                                                                                              \
+        bf16x8 vf[DB];                                                                             \
+        _Pragma("unroll") for (int b = 0; b < DB; ++b)                                             \
+            vf[b] = lo.template tfrag<VOFF + (KSTEP) * 16 * D * 2>(smem, b);                       \
+        f32x16 &sa = sacc[(KSTEP) >> 1];                                                           \
+        _Pragma("unroll") for (int i = 8 * ((KSTEP) & 1); i < 8 * ((KSTEP) & 1) + 8; ++i) {        \
+            const float p = __builtin_amdgcn_exp2f(fmaf(sa[i], c, -mc));                           \
+            sa[i] = p;                                                                             \
+            ls += p;                                                                               \
+        }                                                                                          \
+        const bf16x8 pf = acc_to_frag(sa, (KSTEP) & 1);                                            \
+        _Pragma("unroll") for (int b = 0; b < DB; ++b) oacc[b] = mfma32(vf[b], pf, oacc[b]);       \
     }
+    MOC_PV_STEP(0) MOC_PV_STEP(1) MOC_PV_STEP(2) MOC_PV_STEP(3)
+#undef MOC_PV_STEP
     l_run += ls;
     // 2*DB transposing reads per 16-key step; keep one step of reads in flight
     __builtin_amdgcn_sched_group_barrier(0x100, 4 * DB, 0);
@@ -107,10 +110,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
     constexpr int BN = 64;
     constexpr int KS = D / 16;   // feature steps of the QK product
     constexpr int DB = D / 32;   // 32-feature blocks of the output
-    __shared__ __attribute__((aligned(1024))) bf16_t K0[BN * D];
-    __shared__ __attribute__((aligned(1024))) bf16_t K1[BN * D];
-    __shared__ __attribute__((aligned(1024))) bf16_t V0[BN * D];
-    __shared__ __attribute__((aligned(1024))) bf16_t V1[BN * D];
+    constexpr int TB = BN * D * 2;   // bytes per tile
+    // LDS: K buffers at 0 and TB, V buffers at 2 TB and 3 TB
+    __shared__ __attribute__((aligned(1024))) char smem[4 * TB];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
     const int N = a.N;
@@ -128,7 +130,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
     const int rc = row_valid ? r : it.q_count - 1;
     int qi, slot;
     if (MODE == MODE_ANCHOR) { qi = it.q_start + rc; slot = a.topk; }
-    else { const int e = it.entries[rc]; qi = e / a.topk; slot = e - qi * a.topk; }
+    else { const int e = it.entries[rc]; qi = e >> 5; slot = e & 31; }
 
     const T *qbase = static_cast<const T *>(a.q) + (size_t)bh * N * D;
     const T *kbase = static_cast<const T *>(a.k) + (size_t)bh * N * D;
@@ -143,38 +145,45 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
     for (int b = 0; b < DB; ++b) oacc[b] = zero16();
     float m_run = -INFINITY, l_run = 0.f;
     const float c = a.scale_log2;
+    LaneOffs<D> lo;
+    lo.init(lane);
 
     // Double-buffered pipeline, one barrier per tile: while tile t is consumed
     // from one LDS buffer, tile t+1 streams from global memory into the other.
-    // The loop is unrolled by two so every access names a fixed buffer.
+    // The loop is unrolled by two so every access has a constant buffer offset.
     TileLoader<D, T, BN> kld(tid), vld(tid);
     TileIter<BN> ti(it);
     int valid = ti.valid();
     bool more;
-    auto issue = [&](bf16_t *Kn, bf16_t *Vn) {
+    auto issue = [&](int buf) {
         const size_t st = (size_t)ti.start() * D;
-        kld.issue_rows(kbase + st, ti.valid(), Kn);
-        vld.issue_rows(vbase + st, ti.valid(), Vn);
+        kld.issue_rows(kbase + st, ti.valid(), reinterpret_cast<bf16_t *>(smem + buf * TB));
+        vld.issue_rows(vbase + st, ti.valid(), reinterpret_cast<bf16_t *>(smem + (2 + buf) * TB));
     };
-    auto stage = [&](const bf16_t *Kc, const bf16_t *Vc, bf16_t *Kn, bf16_t *Vn) {
+    auto commit = [&](int buf) {
+        kld.commit(reinterpret_cast<bf16_t *>(smem + buf * TB));
+        vld.commit(reinterpret_cast<bf16_t *>(smem + (2 + buf) * TB));
+    };
+    auto stage = [&](auto cur) {
+        constexpr int CUR = decltype(cur)::value;
         const int cur_valid = valid;
         more = ti.next();
-        if (more) { valid = ti.valid(); issue(Kn, Vn); }
-        if (wave_active) fwd_tile<D>(Kc, Vc, qf, oacc, m_run, l_run, c, cur_valid, lane);
-        if (more) { kld.commit(Kn); vld.commit(Vn); __syncthreads(); }
-        return more;       // false: Kc/Vc held the last tile
+        if (more) { valid = ti.valid(); issue(CUR ^ 1); }
+        if (wave_active)
+            fwd_tile<D, CUR * TB, (2 + CUR) * TB>(smem, lo, qf, oacc, m_run, l_run, c, cur_valid, lane);
+        if (more) { commit(CUR ^ 1); __syncthreads(); }
+        return more;       // false: that was the last tile
     };
-    issue(K0, V0);
-    kld.commit(K0);
-    vld.commit(V0);
+    issue(0);
+    commit(0);
     __syncthreads();
     while (true) {
-        if (!stage(K0, V0, K1, V1)) break;
-        if (!stage(K1, V1, K0, V0)) break;
+        if (!stage(IC<0>{})) break;
+        if (!stage(IC<1>{})) break;
     }
 
     if (!row_valid) return;
-    const float l_tot = l_run + xhalf(l_run);
+    const float l_tot = xhalf_sum(l_run);
     const float inv = 1.f / l_tot;
     const size_t prow = ((size_t)bh * N + qi) * a.slots + slot;
     bf16_t *po = a.po + prow * D;

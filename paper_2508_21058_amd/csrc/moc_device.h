@@ -171,4 +171,60 @@ template <int D> struct SwTile {
     }
 };
 
+// Lane-dependent byte offsets into a SwTile<D>. They do not depend on the tile's
+// base address, on which 32-row block (row reads) or on which 16-row step
+// (transposed reads) is addressed: all of that goes into the instruction's
+// immediate offset, so one set of 8 + 8 registers serves every buffer.
+// pin() hides the values from loop-invariant code motion; without it the
+// compiler materialises one address register per (buffer, block, step).
+template <int D> struct LaneOffs {
+    static constexpr int KS = D / 16, DB = D / 32;
+    int row[KS];        // row operand: row (lane & 31), features [16 s + 8 half, +8)
+    int tr[2 * DB];     // transposed operand: [2 db + second]
+    __device__ __forceinline__ void init(int lane) {
+        const int half = lane >> 5, l32 = lane & 31;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) row[s] = SwTile<D>::off(l32, 2 * s + half) * 2;
+        const int i = lane & 15, bq = (lane >> 4) & 1;
+#pragma unroll
+        for (int u = 0; u < 2 * DB; ++u) {
+            const int x = 32 * (u >> 1) + 16 * bq + 4 * (i & 3);
+            const int r0 = 4 * half + (i >> 2) + 8 * (u & 1);
+            tr[u] = (SwTile<D>::off(r0, x >> 3) + (x & 7)) * 2;
+        }
+    }
+    __device__ __forceinline__ void pin() {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(row[s]));
+#pragma unroll
+        for (int u = 0; u < 2 * DB; ++u) asm volatile("" : "+v"(tr[u]));
+    }
+    // row operand of rows [row0, row0+32) (row0 a multiple of 32) of the tile at byte offset `tile`
+    template <int TILE_ROW0_BYTES>
+    __device__ __forceinline__ bf16x8 frag(const char *smem, int s) const {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(smem + row[s] + TILE_ROW0_BYTES));
+    }
+    // transposed operand, feature block db, source rows [row0, row0+16) (row0 a multiple of 16)
+    template <int TILE_ROW0_BYTES>
+    __device__ __forceinline__ bf16x8 tfrag(const char *smem, int db) const {
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(smem + tr[2 * db] + TILE_ROW0_BYTES));
+        s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(smem + tr[2 * db + 1] + TILE_ROW0_BYTES));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+        return __builtin_bit_cast(bf16x8, r);
+    }
+};
+
+// max (or sum) of a value with its counterpart in the other half-wave, in all
+// lanes, without going through LDS (v_permlane32_swap)
+__device__ __forceinline__ float xhalf_max(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xhalf_sum(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 }  // namespace moc

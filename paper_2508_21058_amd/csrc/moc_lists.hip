@@ -10,7 +10,7 @@
 //   count (LDS histogram per workgroup, one global atomic per non-empty bin)
 //   -> exclusive scan per head (list offsets and tile offsets)
 //   -> fill (LDS ranks + one reservation per bin).
-// An entry is the flat index i*topk + r of sel, i.e. query and slot.
+// An entry packs query and slot as (i << 5) | r (r < MOC_MAX_TOPK = 32).
 #include "moc_device.h"
 #include "moc_internal.h"
 
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void list_scan_kernel(const int32_t *__restric
 }
 
 template <bool LDS_HIST>
-__global__ __launch_bounds__(256) void list_fill_kernel(const int32_t *__restrict__ sel, int NK, int C,
+__global__ __launch_bounds__(256) void list_fill_kernel(const int32_t *__restrict__ sel, int NK, int topk, int C,
                                                         const int32_t *__restrict__ list_off,
                                                         int32_t *__restrict__ cursor,
                                                         int32_t *__restrict__ qlist) {
@@ -130,7 +130,10 @@ __global__ __launch_bounds__(256) void list_fill_kernel(const int32_t *__restric
     for (int u = 0; u < kEntPerThread; ++u) {
         const int e = blockIdx.x * kEntPerWg + u * 256 + threadIdx.x;
         const int j = jj[u];
-        if (j >= 0) ql[lo[j] + (LDS_HIST ? hist[j] : 0) + rk[u]] = e;
+        if (j >= 0) {
+            const int i = e / topk;
+            ql[lo[j] + (LDS_HIST ? hist[j] : 0) + rk[u]] = (i << 5) | (e - i * topk);
+        }
     }
 }
 
@@ -155,8 +158,8 @@ hipError_t launch_build_lists(const moc_meta *m, int BH, int topk, const int32_t
     if (lds) list_count_kernel<true><<<grid, block, shm, st>>>(sel, NK, C, cnt);
     else list_count_kernel<false><<<grid, block, 0, st>>>(sel, NK, C, cnt);
     list_scan_kernel<<<dim3(BH), dim3(256), 0, st>>>(cnt, C, list_off, tile_off);
-    if (lds) list_fill_kernel<true><<<grid, block, shm, st>>>(sel, NK, C, list_off, cursor, qlist);
-    else list_fill_kernel<false><<<grid, block, 0, st>>>(sel, NK, C, list_off, cursor, qlist);
+    if (lds) list_fill_kernel<true><<<grid, block, shm, st>>>(sel, NK, topk, C, list_off, cursor, qlist);
+    else list_fill_kernel<false><<<grid, block, 0, st>>>(sel, NK, topk, C, list_off, cursor, qlist);
     return hipGetLastError();
 }
 
