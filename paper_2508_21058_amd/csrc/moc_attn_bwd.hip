@@ -315,9 +315,14 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
     const float *delta = a.delta + (size_t)bh * N;
 
     // this wave's 32 keys (B operands stay in registers for the whole item)
-    const int nk = min(32, item.key_len - wave * 32);
+    // A tile of <= 32 keys (the ragged tail of a chunk) would leave three waves
+    // idle: instead all four waves take the same keys, split the query blocks
+    // among themselves and add their accumulators at the end.
+    const bool split = item.key_len <= 32;
+    const int kblk = split ? 0 : wave;
+    const int nk = min(32, item.key_len - kblk * 32);
     const bool wave_active = nk > 0;
-    const int key = wave_active ? item.key_start + wave * 32 + min(l32, nk - 1) : item.key_start;
+    const int key = wave_active ? item.key_start + kblk * 32 + min(l32, nk - 1) : item.key_start;
     bf16x8 kf[KS], vf[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -374,11 +379,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
         const int nv = tile_valid(t);
         const bool more = t + 1 < ntiles;
         if (more) issue(t + 1, CUR ^ 1);
-        if (wave_active) {
+        // split mode: wave w takes query block (w & 1) of the steps with parity (w >> 1)
+        const bool do0 = wave_active && (!split || (CUR == (wave >> 1) && (wave & 1) == 0));
+        const bool do1 = wave_active && nv > 32 && (!split || (CUR == (wave >> 1) && (wave & 1) == 1));
+        if (do0)
             dkdv_block<D, CUR * TB, (2 + CUR) * TB, 0>(smem, lo, lse_s[CUR], delta_s[CUR], kf, vf, dkacc, dvacc, c, nv, lane);
-            if (nv > 32)
-                dkdv_block<D, CUR * TB, (2 + CUR) * TB, 32>(smem, lo, lse_s[CUR], delta_s[CUR], kf, vf, dkacc, dvacc, c, nv, lane);
-        }
+        if (do1)
+            dkdv_block<D, CUR * TB, (2 + CUR) * TB, 32>(smem, lo, lse_s[CUR], delta_s[CUR], kf, vf, dkacc, dvacc, c, nv, lane);
         if (more) { commit(CUR ^ 1); __syncthreads(); }
         ++t;
         return more;
@@ -391,6 +398,34 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
         if (!stage(IC<1>{})) break;
     }
 
+    if (split) {
+        // the four waves hold partial sums for the same keys in the same register
+        // layout: exchange them through LDS (16 KB per wave and tensor), wave 0 adds
+        float *xch = reinterpret_cast<float *>(smem);
+        static_assert(4 * DB * 16 * 64 * 4 <= 4 * TB, "exchange buffer must fit the tile buffers");
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            f32x16 *acc = pass == 0 ? dkacc : dvacc;
+            __syncthreads();
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) xch[((wave * DB + b) * 16 + i) * 64 + lane] = acc[b][i];
+            __syncthreads();
+            if (wave == 0) {
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        float v = 0.f;
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) v += xch[((w * DB + b) * 16 + i) * 64 + lane];
+                        acc[b][i] = v;
+                    }
+            }
+        }
+        if (wave != 0) return;
+    }
     if (!wave_active || l32 >= nk) return;
     const float sc = a.scale;
     if (item.partial < 0) {
@@ -406,7 +441,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
                 Io<T>::store4(dv + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
             }
     } else {
-        const size_t prow = ((size_t)bh * a.n_partials + item.partial) * kKeyTile + wave * 32 + l32;
+        const size_t prow = ((size_t)bh * a.n_partials + item.partial) * kKeyTile + kblk * 32 + l32;
         float *pk = a.tpart_k + prow * D, *pv = a.tpart_v + prow * D;
 #pragma unroll
         for (int b = 0; b < DB; ++b)
