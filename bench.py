@@ -63,7 +63,7 @@ def layout_counts(lay, sel, chunk_of_t, topk):
 
 
 def cpu_baseline(lay, cfg, q, k, v, d_o, topk, budget_queries):
-    """Oracle on one head: the queries that attend two sampled video chunks plus
+    """Oracle on one head: the queries that attend eight sampled video chunks plus
     random queries up to `budget_queries`: forward + dQ for those queries, dK/dV
     for the sampled chunks. Algorithmic FLOPs as for the GPU path."""
     from oracle import moc_oracle as mo
@@ -77,7 +77,7 @@ def cpu_baseline(lay, cfg, q, k, v, d_o, topk, budget_queries):
     sel_all, _ = mo.route(L, qn, kbar, topk, True)
     t_route = time.perf_counter() - t0
     video = np.nonzero(L.kind == 0)[0]
-    chunks = np.sort(rng.choice(video[len(video) // 4:], size=min(2, len(video)), replace=False)).astype(np.int32)
+    chunks = np.sort(rng.choice(video[len(video) // 4:], size=min(8, len(video)), replace=False)).astype(np.int32)
     att = np.zeros(N, bool)
     for j in chunks:
         att |= (L.win[L.chunk_of] == L.win[j]) | (sel_all[0, 0] == j).any(-1)
@@ -113,7 +113,7 @@ def main():
     ap.add_argument("--window", default=None, choices=[None, "frame", "shot", "chunk"])
     ap.add_argument("--chunk", type=int, default=None)
     ap.add_argument("--topk", type=int, default=None)
-    ap.add_argument("--cpu-queries", type=int, default=6000, help="oracle sample size (0 = skip the CPU baseline)")
+    ap.add_argument("--cpu-queries", type=int, default=1 << 30, help="oracle sample size, capped at N (0 = skip the CPU baseline)")
     ap.add_argument("--seed", type=int, default=1234)
     args = ap.parse_args()
     if args.gpus != 1:

@@ -1,0 +1,106 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py
+times (all heads, bf16, same seeded device-generated inputs), on sampled
+outputs the oracle can compute one by one:
+
+  - pooled keys of one head, all chunks;
+  - selections of one head, all N queries (tie tolerance as in the small tests);
+  - o, lse, dq at sampled queries of that head;
+  - dk, dv at all tokens of sampled chunks of that head (for the single-shot
+    config also the caption chunk, whose keys are attended by all N queries).
+
+The head checked has the oracle's selection injected before the attention
+calls, so no tie can leak into the attention comparison.
+"""
+import numpy as np
+import pytest
+import torch
+
+import moc_inputs as mi
+from oracle import moc_oracle as mo
+from paper_2508_21058_amd import binding as mb
+from tests.test_gpu_parity import check_close, check_sel
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(workload, window, head, n_sample, with_text_chunk, seed=1234):
+    cfg = mi.CONFIGS[workload]
+    lay = mi.config_layout(workload, window=window)
+    B, H, d, topk, N = cfg["B"], cfg["H"], cfg["d"], cfg["topk"], lay.N
+    q, k, v, d_o = (t.to(torch.bfloat16).contiguous() for t in mi.qkv_do(B, H, N, d, seed, "cuda"))
+    meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
+    pooled, sel = mb.route(meta, q, k, topk, True)
+    torch.cuda.synchronize()
+
+    L = mo.OracleLayout.from_layout(lay)
+    f64 = lambda t: t[0:1, head:head + 1].float().cpu().numpy().astype(np.float64)
+    qn, kn, vn, don = f64(q), f64(k), f64(v), f64(d_o)
+
+    # stage b: pooled keys
+    kbar = mo.pool(L, kn)
+    err = np.abs(pooled[0, head].cpu().numpy() - kbar[0, 0]).max() / np.abs(kbar).max()
+    assert err <= 1e-5, f"pooled keys rel err {err:.3e}"
+
+    # stage c: selections of the whole head
+    sel_ref, _ = mo.route(L, qn, kbar, topk, True)
+    sel_gpu = sel[0, head].cpu().numpy()
+    bad = np.nonzero((np.sort(sel_gpu, -1) != np.sort(sel_ref[0, 0], -1)).any(-1))[0].astype(np.int32)
+    if len(bad):
+        assert len(bad) <= max(2, N // 2000), f"{len(bad)} rows differ"
+        _, sc, _ = mo.route(L, qn, kbar, topk, True, bad, want_scores=True)
+        check_sel(sel_gpu[bad], sel_ref[0, 0][bad], sc[0, 0], topk)
+    # order inside rows (best first) where the sets agree
+    same = np.setdiff1d(np.arange(N), bad)
+    assert (sel_gpu[same] == sel_ref[0, 0][same]).mean() > 0.999
+
+    # stage d with the oracle's selection for this head
+    sel[0, head] = torch.from_numpy(sel_ref[0, 0]).to("cuda")
+    ws = mb.attn_workspace(meta, B, H, d, topk, torch.bfloat16, True)
+    o, lse = mb.attn_fwd(meta, q, k, v, sel, None, ws)
+    dq, dk, dv = mb.attn_bwd(meta, q, k, v, o, lse, d_o, sel, None, ws)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(5)
+    video = np.nonzero(L.kind == 0)[0]
+    chunks = list(rng.choice(video[len(video) // 3:], size=2, replace=False))
+    if with_text_chunk:
+        chunks.append(int(np.nonzero(L.kind == 1)[0][0]))
+    chunks = np.array(sorted(chunks), dtype=np.int32)
+    att = np.zeros(N, bool)
+    for j in chunks:
+        att |= (L.kind[j] == 1) | (L.win[L.chunk_of] == L.win[j]) | (sel_ref[0, 0] == j).any(-1)
+    extra = rng.choice(N, size=n_sample, replace=False)
+    # last queries, first queries, a caption query and random ones are always sampled
+    att[extra] = True
+    att[[0, 1, N - 1, N - 2]] = True
+    qidx = np.nonzero(att)[0].astype(np.int32)
+
+    sel_s = sel_ref[:, :, qidx]
+    o_ref, lse_ref, _ = mo.attn_fwd(L, qn, kn, vn, sel_s, None, qidx)
+    check_close("o", o[0, head].float().cpu().numpy()[qidx], o_ref[0, 0])
+    check_close("lse", lse[0, head].cpu().numpy()[qidx], lse_ref[0, 0])
+    dq_ref = mo.attn_bwd_dq(L, qn, kn, vn, sel_s, o_ref, lse_ref, don[:, :, qidx], None, qidx)
+    check_close("dq", dq[0, head].float().cpu().numpy()[qidx], dq_ref[0, 0])
+
+    o_full = np.zeros((1, 1, N, d)); o_full[0, 0, qidx] = o_ref[0, 0]
+    lse_full = np.zeros((1, 1, N)); lse_full[0, 0, qidx] = lse_ref[0, 0]
+    dk_ref, dv_ref = mo.attn_bwd_dkdv(L, qn, kn, vn, sel_ref, o_full, lse_full, don, None, chunks)
+    rows = np.concatenate([np.arange(L.off[j], L.off[j + 1]) for j in chunks])
+    check_close("dk", dk[0, head].float().cpu().numpy()[rows], dk_ref[0, 0][rows])
+    check_close("dv", dv[0, head].float().cpu().numpy()[rows], dv_ref[0, 0][rows])
+    meta.close()
+
+
+def test_single_shot_config_forward_backward():
+    """BASELINE configs 2/3: 512 text + 21 x 1560 tokens, chunk 260, frame window, k=5, H=24, d=128."""
+    _run("single", None, head=5, n_sample=384, with_text_chunk=True)
+
+
+def test_eight_shot_config_frame_window():
+    """BASELINE config 4 (benchmark workload): 8 x (256 + 9 x 1560) tokens, frame window, k=8."""
+    _run("eight", "frame", head=17, n_sample=384, with_text_chunk=False)
+
+
+def test_eight_shot_config_shot_window():
+    """Config 4 with the whole shot as the forced local window (the multi-shot reading)."""
+    _run("eight", "shot", head=2, n_sample=256, with_text_chunk=False)
