@@ -100,7 +100,13 @@ AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd)
     return L;
 }
 
-RouteWs route_ws_layout(const moc_meta *, int, int, int, int) { return RouteWs{256}; }
+RouteWs route_ws_layout(const moc_meta *m, int BH, int d, int, int) {
+    RouteWs L{};
+    L.Cpad = (m->C + 31) / 32 * 32;
+    L.kb_split = 0;
+    L.total = align_up((size_t)BH * 3 * L.Cpad * d * 2);
+    return L;
+}
 
 }  // namespace moc
 
@@ -249,6 +255,10 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
         }
     }
 
+    std::vector<uint32_t> textmask((C + 31) / 32, 0u);
+    for (int j = 0; j < C; ++j)
+        if (kind[j]) textmask[j >> 5] |= 1u << (j & 31);
+
     moc_meta *m = new (std::nothrow) moc_meta();
     if (!m) return fail(MOC_ERR_HIP, "host allocation failed");
     m->N = N; m->C = C; m->T = T; m->W = W;
@@ -268,7 +278,7 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
                  o_wf = take((size_t)W * 4), o_wl = take((size_t)W * 4), o_aro = take((size_t)(W + 1) * 4),
                  o_ar = take(aranges.size() * sizeof(KeyRange)), o_at = take(atiles.size() * sizeof(AnchorTile)),
                  o_kv = take(kvitems.size() * sizeof(KvItem)), o_tt = take(ttiles.size() * sizeof(TextTile)),
-                 o_cof = take((size_t)N * 4);
+                 o_tm = take(textmask.size() * 4), o_cof = take((size_t)N * 4);
     const size_t upload = o_cof;  // chunk_of is filled on the device
     std::vector<char> host(upload, 0);
     auto put = [&](size_t at, const void *src, size_t bytes) { if (bytes) std::memcpy(host.data() + at, src, bytes); };
@@ -282,6 +292,7 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
     put(o_at, atiles.data(), atiles.size() * sizeof(AnchorTile));
     put(o_kv, kvitems.data(), kvitems.size() * sizeof(KvItem));
     put(o_tt, ttiles.data(), ttiles.size() * sizeof(TextTile));
+    put(o_tm, textmask.data(), textmask.size() * 4);
 
     hipError_t e = hipMalloc(&m->d_base, o);
     if (e != hipSuccess) { delete m; return hip_fail(e, "hipMalloc(meta tables)"); }
@@ -297,6 +308,7 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
     m->d_atiles = reinterpret_cast<AnchorTile *>(base + o_at);
     m->d_kvitems = reinterpret_cast<KvItem *>(base + o_kv);
     m->d_text_tiles = reinterpret_cast<TextTile *>(base + o_tt);
+    m->d_textmask = reinterpret_cast<uint32_t *>(base + o_tm);
     m->d_chunk_of = reinterpret_cast<int32_t *>(base + o_cof);
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -345,14 +357,15 @@ int moc_route(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, 
     if (!q || !k || !pooled_k || (!sel && topk > 0)) return fail(MOC_ERR_NULL, "q, k, pooled_k or sel is NULL");
     if (misaligned(q) || misaligned(k) || misaligned(pooled_k) || misaligned(sel))
         return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
-    const size_t need = moc::route_ws_layout(meta, B * H, d, topk, dtype).total;
-    if (!workspace || workspace_bytes < need) return fail(MOC_ERR_WORKSPACE, "route workspace too small");
+    const moc::RouteWs RL = moc::route_ws_layout(meta, B * H, d, topk, dtype);
+    if (!workspace || workspace_bytes < RL.total) return fail(MOC_ERR_WORKSPACE, "route workspace too small");
     if (misaligned(workspace)) return fail(MOC_ERR_ALIGN, "workspace must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = moc::launch_pool(meta, B * H, d, dtype, k, pooled_k, st);
+    void *kb_split = static_cast<char *>(workspace) + RL.kb_split;
+    hipError_t e = moc::launch_pool(meta, B * H, d, dtype, k, pooled_k, kb_split, RL.Cpad, st);
     if (e != hipSuccess) return hip_fail(e, "pool kernel");
     if (topk > 0) {
-        e = moc::launch_route(meta, B * H, d, dtype, q, pooled_k, topk, causal, sel, st);
+        e = moc::launch_route(meta, B * H, d, dtype, q, kb_split, RL.Cpad, topk, causal, sel, st);
         if (e != hipSuccess) return hip_fail(e, "route kernel");
     }
     return MOC_OK;

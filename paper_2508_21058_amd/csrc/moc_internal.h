@@ -44,6 +44,7 @@ struct moc_meta {
     int32_t *d_wfirst = nullptr;     // [W] first chunk of window
     int32_t *d_wlast = nullptr;      // [W] last chunk of window (inclusive)
     int32_t *d_chunk_of = nullptr;   // [N]
+    uint32_t *d_textmask = nullptr;  // [ceil(C/32)] bit j%32 of word j/32 set: chunk j is text
     int32_t *d_arange_off = nullptr; // [W+1] into d_aranges
     moc::KeyRange *d_aranges = nullptr;
     moc::AnchorTile *d_atiles = nullptr;
@@ -73,14 +74,17 @@ struct AttnWs {
 };
 AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd);
 
-struct RouteWs { size_t total; };
+// Route workspace: pooled keys split into three bf16 planes (hi, mid, lo with
+// hi + mid + lo == the fp32 value), [BH][3][Cpad][d], Cpad = C rounded up to 32, pad rows zero.
+struct RouteWs { size_t kb_split, total; int Cpad; };
 RouteWs route_ws_layout(const moc_meta *m, int BH, int d, int topk, int dtype);
 
 hipError_t launch_chunk_of(const moc_meta *m, hipStream_t st);
 
-hipError_t launch_pool(const moc_meta *m, int BH, int d, int dtype, const void *k, float *kbar, hipStream_t st);
+hipError_t launch_pool(const moc_meta *m, int BH, int d, int dtype, const void *k, float *kbar, void *kb_split,
+                       int Cpad, hipStream_t st);
 
-hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void *q, const float *kbar,
+hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *kb_split, int Cpad,
                         int topk, int causal, int32_t *sel, hipStream_t st);
 
 // counts -> offsets -> inverse lists (per head and chunk: the queries that routed to it)

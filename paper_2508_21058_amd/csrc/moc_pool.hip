@@ -30,13 +30,24 @@ hipError_t launch_chunk_of(const moc_meta *m, hipStream_t st) {
 // One workgroup per (chunk, head). Thread t owns 8 (bf16) or 4 (fp32) features
 // of every (256/TPR)-th row; partial sums are combined through LDS in a fixed
 // order, so the result does not depend on scheduling.
+// Besides the fp32 mean the kernel writes its exact split into three bf16
+// planes (hi + mid + lo == mean) for the matrix-core scoring pass; rows
+// C .. Cpad-1 of the planes are zero.
 template <int D, typename T>
 __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ k, const int32_t *__restrict__ off,
-                                                   int N, int C, float *__restrict__ kbar) {
+                                                   int N, int C, int Cpad, float *__restrict__ kbar,
+                                                   bf16_t *__restrict__ split) {
     constexpr int VEC = 16 / sizeof(T);      // elements per 16-byte load
     constexpr int TPR = D / VEC;             // threads per row
     constexpr int RPP = 256 / TPR;           // rows per pass
     const int j = blockIdx.x, bh = blockIdx.y;
+    if (j >= C) {
+        if (threadIdx.x < D) {
+#pragma unroll
+            for (int p = 0; p < 3; ++p) split[(((size_t)bh * 3 + p) * Cpad + j) * D + threadIdx.x] = (bf16_t)0.f;
+        }
+        return;
+    }
     const int t0 = off[j], t1 = off[j + 1];
     const int cg = threadIdx.x % TPR, r0 = threadIdx.x / TPR;
     const T *base = k + ((size_t)bh * N) * D + cg * VEC;
@@ -80,15 +91,25 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ k, cons
         float s = 0.f;
 #pragma unroll 4
         for (int r = 0; r < RPP; ++r) s += red[r][threadIdx.x];
-        kbar[((size_t)bh * C + j) * D + threadIdx.x] = s / (float)(t1 - t0);
+        const float mean = s / (float)(t1 - t0);
+        kbar[((size_t)bh * C + j) * D + threadIdx.x] = mean;
+        const bf16_t hi = (bf16_t)mean;
+        const float r1 = mean - (float)hi;
+        const bf16_t mid = (bf16_t)r1;
+        const bf16_t lo = (bf16_t)(r1 - (float)mid);
+        split[(((size_t)bh * 3 + 0) * Cpad + j) * D + threadIdx.x] = hi;
+        split[(((size_t)bh * 3 + 1) * Cpad + j) * D + threadIdx.x] = mid;
+        split[(((size_t)bh * 3 + 2) * Cpad + j) * D + threadIdx.x] = lo;
     }
 }
 
-hipError_t launch_pool(const moc_meta *m, int BH, int d, int dtype, const void *k, float *kbar, hipStream_t st) {
-    dim3 grid(m->C, BH), block(256);
+hipError_t launch_pool(const moc_meta *m, int BH, int d, int dtype, const void *k, float *kbar, void *kb_split,
+                       int Cpad, hipStream_t st) {
+    dim3 grid(Cpad, BH), block(256);
     MOC_PROF("pool", st);
 #define MOC_POOL(DD, TT) \
-    pool_kernel<DD, TT><<<grid, block, 0, st>>>(static_cast<const TT *>(k), m->d_off, m->N, m->C, kbar)
+    pool_kernel<DD, TT><<<grid, block, 0, st>>>(static_cast<const TT *>(k), m->d_off, m->N, m->C, Cpad, kbar, \
+                                                static_cast<bf16_t *>(kb_split))
     if (dtype == MOC_BF16) { if (d == 128) MOC_POOL(128, bf16_t); else MOC_POOL(64, bf16_t); }
     else { if (d == 128) MOC_POOL(128, float); else MOC_POOL(64, float); }
 #undef MOC_POOL

@@ -2,108 +2,294 @@
 // routing mask; Sec. 3.3 pre-routing mask that removes forced links from the
 // candidates).
 //
-// One lane per query. The query row lives in registers (fp32); pooled keys are
-// wave-uniform and arrive through scalar loads; scores are accumulated in fp32
-// and never written to memory. Each lane keeps its top-k as a register-resident
-// list sorted by (score desc, index asc); chunks are visited in ascending index
-// order and a candidate must beat the list strictly, so ties keep the lower
-// index. Causality bounds the chunk loop per wave.
-#include "moc_device.h"
-#include "moc_internal.h"
+// Scores on matrix cores at fp32 accuracy: the fp32 pooled keys arrive split
+// into three bf16 planes (hi + mid + lo == value); a bf16 query is exact, an
+// fp32 query is split the same way, and all partial products of order <= 2 are
+// accumulated in fp32, so a score differs from the exact inner product only by
+// accumulation rounding. S^T[chunk][query] tiles of 32 chunks x 32 queries put
+// one query in each lane (two half-waves share a query and own 16 chunks of a
+// tile each); the [N, C] score matrix never exists in memory.
+//
+// Per-lane top-k without a sort and without paying wave divergence per score:
+//   pass 1  per lane, the top-k of the TILE MAXIMA (values only, a min/max
+//           network): its k-th entry is a lower bound tau of the k-th best score;
+//   pass 2  scores are recomputed (cheap on matrix cores), those >= tau (few)
+//           are appended to a per-lane queue in LDS;
+//   drain   the queue is inserted into a register-resident sorted list with
+//           strict comparisons, in chunk order, so ties keep the lower index;
+//   merge   the two half-waves exchange their lists.
+// A full queue is drained on the spot, so any data (ties, few tiles) stays exact.
+#include "moc_attn_common.h"
 
 namespace moc {
 
-template <int D, typename T, int KMAX>
-__global__ __launch_bounds__(256) void route_kernel(const T *__restrict__ q, const float *__restrict__ kbar,
-                                                    const int32_t *__restrict__ chunk_of,
-                                                    const int32_t *__restrict__ kind,
-                                                    const int32_t *__restrict__ win,
-                                                    const int32_t *__restrict__ wfirst,
-                                                    const int32_t *__restrict__ wlast, int N, int C, int topk,
-                                                    int causal, int32_t *__restrict__ sel) {
-    const int bh = blockIdx.y;
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    const bool valid = i < N;
-    const int ic = valid ? i : N - 1;
-    const int cq = chunk_of[ic];
-    const int w = win[cq];
-    const int wf = wfirst[w], wl = wlast[w];
-    const int limit = causal ? cq : C;           // candidates have index < limit
-    // queries of a wave are consecutive, so the last lane has the largest limit
-    const int jmax = __shfl(limit, 63, 64);
+struct RouteArgs {
+    const void *q;
+    const bf16_t *split;          // [BH][3][Cpad][D]
+    const int32_t *chunk_of, *win, *wfirst, *wlast;
+    const uint32_t *textmask;
+    int32_t *sel;
+    int N, C, Cpad, topk, causal;
+};
 
-    float qf[D];
-    {
-        const T *qp = q + ((size_t)bh * N + ic) * D;
-#pragma unroll
-        for (int x = 0; x < D; x += 8) Io<T>::load8f(qp + x, qf + x);
-    }
+constexpr int kQCap = 16;         // queue entries per lane
 
-    // right-aligned list: positions [KMAX-topk, KMAX) hold the current best in
-    // descending order; the others hold +inf and are never displaced
-    float val[KMAX];
-    int idx[KMAX];
-    const int base = KMAX - topk;
+// sorted insert, strict: an equal score stays behind the entries already there
+template <int KMAX>
+__device__ __forceinline__ void topk_insert(float (&val)[KMAX], int (&idx)[KMAX], float x, int xi) {
 #pragma unroll
     for (int p = 0; p < KMAX; ++p) {
-        val[p] = (p >= base) ? -INFINITY : INFINITY;
-        idx[p] = -1;
+        const bool sw = x > val[p];
+        const float tv = val[p];
+        const int ti = idx[p];
+        val[p] = sw ? x : tv;
+        idx[p] = sw ? xi : ti;
+        x = sw ? tv : x;
+        xi = sw ? ti : xi;
+    }
+}
+
+// sorted insert ordering by (score desc, index asc)
+template <int KMAX>
+__device__ __forceinline__ void topk_insert_tie(float (&val)[KMAX], int (&idx)[KMAX], float x, int xi) {
+#pragma unroll
+    for (int p = 0; p < KMAX; ++p) {
+        const bool sw = (x > val[p]) || (x == val[p] && (unsigned)xi < (unsigned)idx[p]);
+        const float tv = val[p];
+        const int ti = idx[p];
+        val[p] = sw ? x : tv;
+        idx[p] = sw ? xi : ti;
+        x = sw ? tv : x;
+        xi = sw ? ti : xi;
+    }
+}
+
+template <int D, typename T, int KMAX>
+__global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
+    constexpr int KS = D / 16;
+    constexpr int NQ = sizeof(T) == 2 ? 1 : 3;       // query planes
+    constexpr int PB = 32 * D * 2;                   // bytes of one plane tile (32 chunks)
+    constexpr int TB = 3 * PB;                       // bytes of one staged tile
+    __shared__ __attribute__((aligned(1024))) char smem[2 * TB];
+    __shared__ float qs[kQCap][256];
+    __shared__ int32_t qidx[kQCap][256];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int bh = blockIdx.y, N = a.N, C = a.C;
+    const int q0 = blockIdx.x * 128;
+    const int i = q0 + wave * 32 + l32;
+    const bool valid = i < N;
+    const int ic = valid ? i : N - 1;
+    const int cq = a.chunk_of[ic];
+    const int w = a.win[cq];
+    const int wf = a.wfirst[w], wl = a.wlast[w];
+    const int limit = a.causal ? cq : C;                               // candidates have index < limit
+    // queries ascend with the lane, so do chunk, window and limit
+    const int lim_wg = a.causal ? a.chunk_of[min(q0 + 127, N - 1)] : C;  // uniform: largest limit in the workgroup
+    const int ntiles = (lim_wg + 31) >> 5;
+    const int lim_lo = __shfl(limit, 0, 64);                            // smallest limit in the wave
+    const int wf_lo = __shfl(wf, 0, 64), wl_hi = __shfl(wl, 31, 64);    // chunks that may be forced links in the wave
+    const int topk = a.topk;
+    int32_t *out = a.sel + ((size_t)bh * N + ic) * topk;
+    if (ntiles == 0) {                                                  // no candidates at all
+        if (valid && half == 0)
+            for (int r = 0; r < topk; ++r) out[r] = -1;
+        return;
     }
 
-    const float *kb_bh = kbar + (size_t)bh * C * D;
-    for (int j0 = 0; j0 < jmax; j0 += 4) {
-        float s[4] = {0.f, 0.f, 0.f, 0.f};
-        const float *kb[4];
+    // query operand planes (B operand: lane -> query column)
+    bf16x8 qf[NQ][KS];
+    {
+        const T *qp = static_cast<const T *>(a.q) + ((size_t)bh * N + ic) * D;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) kb[u] = kb_bh + (size_t)min(j0 + u, C - 1) * D;
+        for (int s = 0; s < KS; ++s) {
+            if constexpr (NQ == 1) {
+                qf[0][s] = Io<T>::load8(qp + s * 16 + half * 8);
+            } else {
+                float f[8];
+                Io<T>::load8f(qp + s * 16 + half * 8, f);
+                float hi[8], mid[8], lo[8];
 #pragma unroll
-        for (int x = 0; x < D; ++x) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) s[u] = fmaf(qf[x], kb[u][x], s[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int j = j0 + u;
-            if (j >= jmax) break;                 // uniform
-            if (kind[j]) continue;                // uniform: text is a forced link
-            const bool elig = (j < limit) && (j < wf || j > wl);
-            if (elig && s[u] > val[KMAX - 1]) {
-                float x = s[u];
-                int xi = j;
-#pragma unroll
-                for (int p = 0; p < KMAX; ++p) {
-                    const bool sw = x > val[p];
-                    const float tv = val[p];
-                    const int ti = idx[p];
-                    val[p] = sw ? x : tv;
-                    idx[p] = sw ? xi : ti;
-                    x = sw ? tv : x;
-                    xi = sw ? ti : xi;
+                for (int e = 0; e < 8; ++e) {
+                    const bf16_t h = (bf16_t)f[e];
+                    const float r1 = f[e] - (float)h;
+                    const bf16_t m = (bf16_t)r1;
+                    hi[e] = (float)h; mid[e] = (float)m; lo[e] = r1 - (float)m;
                 }
+                u32x4 ph, pm, pl;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    ph[e] = pack_bf16(hi[2 * e], hi[2 * e + 1]);
+                    pm[e] = pack_bf16(mid[2 * e], mid[2 * e + 1]);
+                    pl[e] = pack_bf16(lo[2 * e], lo[2 * e + 1]);
+                }
+                qf[0][s] = __builtin_bit_cast(bf16x8, ph);
+                qf[NQ > 1 ? 1 : 0][s] = __builtin_bit_cast(bf16x8, pm);
+                qf[NQ > 2 ? 2 : 0][s] = __builtin_bit_cast(bf16x8, pl);
             }
         }
     }
-    if (valid) {
-        int32_t *out = sel + ((size_t)bh * N + i) * topk;
+    LaneOffs<D> lo;
+    lo.init(lane);
+
+    TileLoader<D, bf16_t, 32> ld(tid);
+    const bf16_t *sp = a.split + (size_t)bh * 3 * a.Cpad * D;
+    auto issue = [&](int t, int buf) {
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+            ld.issue_rows(sp + ((size_t)p * a.Cpad + t * 32) * D, 32, reinterpret_cast<bf16_t *>(smem + buf * TB + p * PB));
+    };
+
+    // scores of tile t for this lane: 16 chunks, ineligible ones set to -inf
+    auto scores = [&](auto cur, int t) -> f32x16 {
+        constexpr int CUR = decltype(cur)::value;
+        lo.pin();
+        f32x16 acc = zero16();
+#pragma unroll
+        for (int qa = 0; qa < NQ; ++qa)
+#pragma unroll
+            for (int kp = 0; kp < 3; ++kp) {
+                if (qa + kp > 2) continue;
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    bf16x8 kf;
+                    if (kp == 0) kf = lo.template frag<CUR * TB>(smem, s);
+                    else if (kp == 1) kf = lo.template frag<CUR * TB + PB>(smem, s);
+                    else kf = lo.template frag<CUR * TB + 2 * PB>(smem, s);
+                    acc = mfma32(kf, qf[qa][s], acc);
+                }
+            }
+        const int j0 = t * 32;
+        const uint32_t tm = a.textmask[t];
+        // fast path: the whole tile is a candidate for every query of the wave
+        const bool clean = tm == 0 && j0 + 32 <= lim_lo && (j0 + 32 <= wf_lo || j0 > wl_hi);
+        if (!clean) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int bit = (r >> 2) * 8 + half * 4 + (r & 3);
+                const int j = j0 + bit;
+                const bool ok = j < limit && (j < wf || j > wl) && !((tm >> bit) & 1u);
+                if (!ok) acc[r] = -INFINITY;
+            }
+        }
+        return acc;
+    };
+
+    // ---------------- pass 1: per-lane top-k of tile maxima -> lower bound tau
+    // right-aligned value list: [KMAX-topk, KMAX) descending, the rest +inf
+    float tv[KMAX];
+    const int base = KMAX - topk;
+#pragma unroll
+    for (int p = 0; p < KMAX; ++p) tv[p] = (p >= base) ? -INFINITY : INFINITY;
+    auto pass1 = [&](auto cur, int t) {
+        constexpr int CUR = decltype(cur)::value;
+        const bool more = t + 1 < ntiles;
+        if (more) issue(t + 1, CUR ^ 1);
+        const f32x16 sc = scores(cur, t);
+        float x = sc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) x = fmaxf(x, sc[r]);
+#pragma unroll
+        for (int p = 0; p < KMAX; ++p) {
+            const float hi = fmaxf(tv[p], x);
+            x = fminf(tv[p], x);
+            tv[p] = hi;
+        }
+        if (more) __syncthreads();
+        return more;
+    };
+    issue(0, 0);
+    __syncthreads();
+    for (int t = 0;;) {
+        if (!pass1(IC<0>{}, t++)) break;
+        if (!pass1(IC<1>{}, t++)) break;
+    }
+    // both half-waves hold a valid bound for the query; never let -inf pass the filter
+    float tau = fmaxf(xhalf_max(tv[KMAX - 1]), -3.0e38f);
+
+    // ---------------- pass 2: collect scores >= tau, keep an exact sorted list
+    float val[KMAX];
+    int idx[KMAX];
+#pragma unroll
+    for (int p = 0; p < KMAX; ++p) { val[p] = (p >= base) ? -INFINITY : INFINITY; idx[p] = -1; }
+    int cnt = 0;
+    auto drain = [&]() {
+        int mx = cnt;
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) mx = max(mx, __shfl_xor(mx, o, 64));
+        for (int e = 0; e < mx; ++e) {
+            const bool has = e < cnt;
+            const float x = has ? qs[e][tid] : -INFINITY;
+            const int xi = has ? qidx[e][tid] : -1;
+            topk_insert<KMAX>(val, idx, x, xi);
+        }
+        cnt = 0;
+        tau = fmaxf(tau, val[KMAX - 1]);     // once the list is full its tail bounds the k-th best
+    };
+    auto pass2 = [&](auto cur, int t) {
+        constexpr int CUR = decltype(cur)::value;
+        const bool more = t + 1 < ntiles;
+        if (more) issue(t + 1, CUR ^ 1);
+        const f32x16 sc = scores(cur, t);
+        int np = 0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) np += sc[r] >= tau ? 1 : 0;
+        if (__any(cnt + np > kQCap)) drain();   // make room (the bound may rise, fewer scores pass)
+        const int j0 = t * 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            if (sc[r] >= tau) {
+                qs[cnt][tid] = sc[r];
+                qidx[cnt][tid] = j0 + (r >> 2) * 8 + half * 4 + (r & 3);
+                ++cnt;
+            }
+        }
+        if (more) __syncthreads();
+        return more;
+    };
+    __syncthreads();
+    issue(0, 0);
+    __syncthreads();
+    for (int t = 0;;) {
+        if (!pass2(IC<0>{}, t++)) break;
+        if (!pass2(IC<1>{}, t++)) break;
+    }
+    drain();
+
+    // ---------------- merge the two half-waves (score desc, index asc)
+    {
+        float ov[KMAX];
+        int oi[KMAX];
+#pragma unroll
+        for (int p = 0; p < KMAX; ++p) { ov[p] = xhalf(val[p]); oi[p] = __shfl_xor(idx[p], 32, 64); }
+#pragma unroll
+        for (int p = 0; p < KMAX; ++p)
+            if (p >= base) topk_insert_tie<KMAX>(val, idx, ov[p], oi[p]);
+    }
+    if (valid && half == 0) {
 #pragma unroll
         for (int p = 0; p < KMAX; ++p)
             if (p >= base) out[p - base] = idx[p];
     }
 }
 
-hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void *q, const float *kbar, int topk,
-                        int causal, int32_t *sel, hipStream_t st) {
-    dim3 grid((m->N + 255) / 256, BH), block(256);
+hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *kb_split, int Cpad,
+                        int topk, int causal, int32_t *sel, hipStream_t st) {
+    RouteArgs a{};
+    a.q = q;
+    a.split = static_cast<const bf16_t *>(kb_split);
+    a.chunk_of = m->d_chunk_of; a.win = m->d_win; a.wfirst = m->d_wfirst; a.wlast = m->d_wlast;
+    a.textmask = m->d_textmask;
+    a.sel = sel;
+    a.N = m->N; a.C = m->C; a.Cpad = Cpad; a.topk = topk; a.causal = causal != 0;
+    dim3 grid((m->N + 127) / 128, BH), block(256);
     MOC_PROF("route_topk", st);
-#define MOC_ROUTE(DD, TT, KK)                                                                              \
-    route_kernel<DD, TT, KK><<<grid, block, 0, st>>>(static_cast<const TT *>(q), kbar, m->d_chunk_of, m->d_kind, \
-                                                     m->d_win, m->d_wfirst, m->d_wlast, m->N, m->C, topk,  \
-                                                     causal != 0, sel)
-#define MOC_ROUTE_K(DD, TT)                      \
-    do {                                         \
-        if (topk <= 8) MOC_ROUTE(DD, TT, 8);     \
+#define MOC_ROUTE(DD, TT, KK) route_kernel<DD, TT, KK><<<grid, block, 0, st>>>(a)
+#define MOC_ROUTE_K(DD, TT)                         \
+    do {                                            \
+        if (topk <= 8) MOC_ROUTE(DD, TT, 8);        \
         else if (topk <= 16) MOC_ROUTE(DD, TT, 16); \
-        else MOC_ROUTE(DD, TT, 32);              \
+        else MOC_ROUTE(DD, TT, 32);                 \
     } while (0)
     if (dtype == MOC_BF16) { if (d == 128) MOC_ROUTE_K(128, bf16_t); else MOC_ROUTE_K(64, bf16_t); }
     else { if (d == 128) MOC_ROUTE_K(128, float); else MOC_ROUTE_K(64, float); }
