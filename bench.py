@@ -207,12 +207,13 @@ def main():
         ach = alg[dom][1] / (kernels[dom]["ms"] * 1e-3) / 1e9
         roof = dict(kernel=dom, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                     frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, avg_ms=kernels[dom]["ms"])
-    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled); see profiles/
+    tfile = os.path.join(ROOT, "profiles", "moc_kernels_eight_shot_frame_window.txt")
     if os.path.exists(tfile):
-        with open(tfile) as f:
-            tr = json.load(f)
-        key = f"{args.workload}:{lay.meta.get('window')}:{dom}"
-        roof["traffic"] = tr.get(key)
+        key = f"traffic {args.workload}:{lay.meta.get('window')}:{dom} ="
+        for line in open(tfile):
+            if line.startswith(key):
+                roof["traffic"] = {"hbm_GB_per_launch": float(line.split("=")[1]), "source": "profiles/" + os.path.basename(tfile)}
 
     out = {
         "metric": "routed_attn_tflops_fwd_bwd", "value": round(total_flops / (ms_step * 1e-3) / 1e12, 2),
