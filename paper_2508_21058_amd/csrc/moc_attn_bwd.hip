@@ -23,7 +23,8 @@ namespace moc {
 // ------------------------------------------------------------------ delta
 template <int D, typename T>
 __global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ o, const T *__restrict__ d_o, size_t rows,
-                                                    float *__restrict__ delta) {
+                                                    const float *__restrict__ lse, float *__restrict__ delta,
+                                                    float *__restrict__ lse2) {
     constexpr int TPQ = D / 8, QPW = 256 / TPQ;
     const size_t row = (size_t)blockIdx.x * QPW + threadIdx.x / TPQ;
     const int c8 = threadIdx.x % TPQ;
@@ -37,7 +38,7 @@ __global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ o, con
     }
 #pragma unroll
     for (int w = TPQ / 2; w >= 1; w >>= 1) s += __shfl_xor(s, w, 64);
-    if (row < rows && c8 == 0) delta[row] = s;
+    if (row < rows && c8 == 0) { delta[row] = s; lse2[row] = lse[row] * kLog2e; }
 }
 
 // ------------------------------------------------------------------ dQ pass
@@ -218,7 +219,8 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const bf16_t *__restrict_
 // ------------------------------------------------------------------ dK/dV pass
 struct KvArgs {
     const void *q, *k, *v, *d_o;
-    const float *lse, *delta;
+    const float *lse, *delta, *lse2;   // lse2 = lse * log2(e)
+    const float *glse, *gdelta;        // lse2 / delta gathered in the order of the inverse lists
     void *dk, *dv;
     float *tpart_k, *tpart_v;
     const KvItem *items;
@@ -291,6 +293,8 @@ __device__ __forceinline__ void dkdv_block(const char *smem, LaneOffs<D> &lo, co
 #undef MOC_KV_STEP
 }
 
+// Register-staged, double-buffered variant: used for fp32 storage (which must be
+// converted on the way into LDS).
 template <int D, typename T>
 __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
     constexpr int BQ = 64;
@@ -455,6 +459,202 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
     }
 }
 
+// lse2 and delta of the queries of every inverse list, in list order, so the
+// key-stationary pass reads them as contiguous vectors
+__global__ __launch_bounds__(256) void gather_stats_kernel(const int32_t *__restrict__ qlist,
+                                                           const int32_t *__restrict__ list_off, int N, int NK, int C,
+                                                           const float *__restrict__ lse2,
+                                                           const float *__restrict__ delta, float *__restrict__ glse,
+                                                           float *__restrict__ gdelta) {
+    const int bh = blockIdx.y;
+    const int pos = blockIdx.x * 256 + threadIdx.x;
+    if (pos >= list_off[(size_t)bh * (C + 1) + C]) return;
+    const int i = qlist[(size_t)bh * NK + pos] >> 5;
+    glse[(size_t)bh * NK + pos] = lse2[(size_t)bh * N + i];
+    gdelta[(size_t)bh * NK + pos] = delta[(size_t)bh * N + i];
+}
+
+// s_waitcnt that only bounds the number of outstanding vector-memory operations
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// bf16 storage: the query stream of an item is mostly a gather of rows scattered
+// over the sequence, so one tile of look-ahead does not cover the memory
+// latency. This variant keeps NS - 1 tiles of asynchronous global->LDS loads in
+// flight: before tile t is consumed the wave waits only until its own loads of
+// tile t have landed (vmcnt bound, no drain), then one barrier publishes the tile
+// and frees the buffer of tile t-1 for the loads of tile t+NS-1. Everything the
+// loop loads, per-query lse and delta included, goes through the async path, so
+// no register-destination load forces an early wait.
+template <int D>
+__global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
+    typedef bf16_t T;
+    constexpr int BQ = 64, NS = 4;
+    constexpr int KS = D / 16, DB = D / 32;
+    constexpr int TB = BQ * D * 2;                 // bytes of one Q (or dO) tile
+    constexpr int SB = 2 * TB;                     // bytes of one stage: Q tile, dO tile
+    constexpr int LPT = 2 * (BQ * D * 2 / 1024 / 4) + 2;   // async loads per wave and tile
+    __shared__ __attribute__((aligned(1024))) char smem[NS * SB];
+    __shared__ __attribute__((aligned(256))) float lse_s[NS][BQ], delta_s[NS][BQ];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    const int N = a.N;
+    int logical;
+    if (!xcd_remap((long long)a.n_items * a.BH, logical)) return;
+    const int bh = logical / a.n_items;
+    const KvItem item = a.items[logical - bh * a.n_items];
+
+    const T *qbase = static_cast<const T *>(a.q) + (size_t)bh * N * D;
+    const T *kbase = static_cast<const T *>(a.k) + (size_t)bh * N * D;
+    const T *vbase = static_cast<const T *>(a.v) + (size_t)bh * N * D;
+    const T *dobase = static_cast<const T *>(a.d_o) + (size_t)bh * N * D;
+    const float *lse2 = a.lse2 + (size_t)bh * N;
+    const float *delta = a.delta + (size_t)bh * N;
+
+    const bool split = item.key_len <= 32;         // see the register-staged variant
+    const int kblk = split ? 0 : wave;
+    const int nk = min(32, item.key_len - kblk * 32);
+    const bool wave_active = nk > 0;
+    const int key = wave_active ? item.key_start + kblk * 32 + min(l32, nk - 1) : item.key_start;
+    bf16x8 kf[KS], vf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        kf[s] = Io<T>::load8(kbase + (size_t)key * D + s * 16 + half * 8);
+        vf[s] = Io<T>::load8(vbase + (size_t)key * D + s * 16 + half * 8);
+    }
+    f32x16 dkacc[DB], dvacc[DB];
+#pragma unroll
+    for (int b = 0; b < DB; ++b) { dkacc[b] = zero16(); dvacc[b] = zero16(); }
+    LaneOffs<D> lo;
+    lo.init(lane);
+
+    const int nA = (item.q_len + BQ - 1) / BQ;
+    // all of these are plain values (never reassigned), so nothing of the loop state lives in memory
+    const bool routed = item.chunk >= 0 && a.topk > 0;
+    const int32_t *loff = a.list_off + (size_t)bh * (a.C + 1);
+    const int lbeg = routed ? loff[item.chunk] : 0;
+    const int cntB = routed ? loff[item.chunk + 1] - lbeg : 0;
+    const size_t lpos = (size_t)bh * N * a.topk + lbeg;
+    const int32_t *const entries = a.qlist + lpos;
+    const float *const glse = a.glse + lpos;
+    const float *const gdelta = a.gdelta + lpos;
+    const int ntiles = nA + (cntB + BQ - 1) / BQ;
+    if (ntiles == 0) return;
+
+    TileLoader<D, T, BQ> ld(tid);
+    auto tile_valid = [&](int t) { return t < nA ? min(BQ, item.q_len - t * BQ) : min(BQ, cntB - (t - nA) * BQ); };
+    // every wave issues exactly LPT async loads per tile
+    auto issue = [&](int t, int st) {
+        const int nv = tile_valid(t);
+        bf16_t *qdst = reinterpret_cast<bf16_t *>(smem + st * SB);
+        bf16_t *dodst = reinterpret_cast<bf16_t *>(smem + st * SB + TB);
+        const int r16 = min(wave * 16 + (lane & 15), nv - 1);    // this wave's 16 rows of the lse / delta vectors
+        const bool contig = t < nA;
+        const int q0 = item.q_start + t * BQ, g0 = (t - nA) * BQ;
+        if (contig) {
+            ld.issue_rows(qbase + (size_t)q0 * D, nv, qdst);
+            ld.issue_rows(dobase + (size_t)q0 * D, nv, dodst);
+        } else {
+            const auto lr = ld.list_rows(entries + g0, nv);
+            ld.issue_list(qbase, lr, qdst);
+            ld.issue_list(dobase, lr, dodst);
+        }
+        const float *lp = (contig ? lse2 + q0 : glse + g0) + r16;
+        const float *dp = (contig ? delta + q0 : gdelta + g0) + r16;
+        if (lane < 16) {
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)lp,
+                                             (__attribute__((address_space(3))) void *)(&lse_s[st][wave * 16]), 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)dp,
+                                             (__attribute__((address_space(3))) void *)(&delta_s[st][wave * 16]), 4, 0, 0);
+        }
+    };
+
+    const float c = a.scale_log2;
+    wait_vmcnt<0>();     // K / V fragments are in registers before the asynchronous stream starts
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p)
+        if (p < ntiles) issue(p, p);
+    for (int t = 0; t < ntiles; ++t) {
+        const int st = t % NS;
+        // tile t complete for this wave: at most the loads of the younger tiles may be outstanding
+        const int younger = min(NS - 2, ntiles - 1 - t);
+        if (younger >= 2) wait_vmcnt<2 * LPT>();
+        else if (younger == 1) wait_vmcnt<LPT>();
+        else wait_vmcnt<0>();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (t + NS - 1 < ntiles) issue(t + NS - 1, (t + NS - 1) % NS);
+        const int nv = tile_valid(t);
+        LaneOffs<D> lc = lo;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) lc.row[s] += st * SB;
+#pragma unroll
+        for (int u = 0; u < 2 * DB; ++u) lc.tr[u] += st * SB;
+        const bool mine = !split || (t & 1) == (wave >> 1);
+        const bool do0 = wave_active && mine && (!split || (wave & 1) == 0);
+        const bool do1 = wave_active && mine && nv > 32 && (!split || (wave & 1) == 1);
+        if (do0) dkdv_block<D, 0, TB, 0>(smem, lc, lse_s[st], delta_s[st], kf, vf, dkacc, dvacc, c, nv, lane);
+        if (do1) dkdv_block<D, 0, TB, 32>(smem, lc, lse_s[st], delta_s[st], kf, vf, dkacc, dvacc, c, nv, lane);
+    }
+
+    if (split) {
+        float *xch = reinterpret_cast<float *>(smem);
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            f32x16 *acc = pass == 0 ? dkacc : dvacc;
+            __syncthreads();
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) xch[((wave * DB + b) * 16 + i) * 64 + lane] = acc[b][i];
+            __syncthreads();
+            if (wave == 0) {
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        float v = 0.f;
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) v += xch[((w * DB + b) * 16 + i) * 64 + lane];
+                        acc[b][i] = v;
+                    }
+            }
+        }
+        if (wave != 0) return;
+    }
+    if (!wave_active || l32 >= nk) return;
+    const float sc = a.scale;
+    if (item.partial < 0) {
+        T *dk = static_cast<T *>(a.dk) + ((size_t)bh * N + key) * D;
+        T *dv = static_cast<T *>(a.dv) + ((size_t)bh * N + key) * D;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int x = b * 32 + g * 8 + half * 4;
+                Io<T>::store4(dk + x, dkacc[b][4 * g] * sc, dkacc[b][4 * g + 1] * sc, dkacc[b][4 * g + 2] * sc,
+                              dkacc[b][4 * g + 3] * sc);
+                Io<T>::store4(dv + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
+            }
+    } else {
+        const size_t prow = ((size_t)bh * a.n_partials + item.partial) * kKeyTile + kblk * 32 + l32;
+        float *pk = a.tpart_k + prow * D, *pv = a.tpart_v + prow * D;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int x = b * 32 + g * 8 + half * 4;
+                Io<float>::store4(pk + x, dkacc[b][4 * g] * sc, dkacc[b][4 * g + 1] * sc, dkacc[b][4 * g + 2] * sc,
+                                  dkacc[b][4 * g + 3] * sc);
+                Io<float>::store4(pv + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
+            }
+    }
+}
+
 // sums the per-segment partials of a text key tile in a fixed order
 template <int D, typename T>
 __global__ __launch_bounds__(256) void text_reduce_kernel(const float *__restrict__ tpart_k,
@@ -485,9 +685,19 @@ static hipError_t bwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, KvArgs &kv
     const size_t rows = (size_t)BH * m->N;
     { MOC_PROF("delta", st);
     delta_kernel<D, T><<<dim3((unsigned)((rows + QPW - 1) / QPW)), dim3(256), 0, st>>>(
-        static_cast<const T *>(o), static_cast<const T *>(a.d_o), rows, const_cast<float *>(a.delta)); }
+        static_cast<const T *>(o), static_cast<const T *>(a.d_o), rows, a.lse, const_cast<float *>(a.delta),
+        const_cast<float *>(kv.lse2)); }
     { MOC_PROF("attn_bwd_dkdv", st);
-    attn_bwd_dkdv_kernel<D, T><<<dim3(xcd_grid((long long)m->n_kvitems * BH)), dim3(256), 0, st>>>(kv); }
+    if constexpr (sizeof(T) == 2) {
+        if (a.topk > 0) {
+            const int NK = m->N * a.topk;
+            gather_stats_kernel<<<dim3((NK + 255) / 256, BH), dim3(256), 0, st>>>(
+                kv.qlist, kv.list_off, m->N, NK, m->C, kv.lse2, kv.delta, const_cast<float *>(kv.glse),
+                const_cast<float *>(kv.gdelta));
+        }
+        attn_bwd_dkdv_pipe_kernel<D><<<dim3(xcd_grid((long long)m->n_kvitems * BH)), dim3(256), 0, st>>>(kv);
+    } else
+        attn_bwd_dkdv_kernel<D, T><<<dim3(xcd_grid((long long)m->n_kvitems * BH)), dim3(256), 0, st>>>(kv); }
     if (m->n_text_tiles > 0) { MOC_PROF("text_reduce", st);
         text_reduce_kernel<D, T><<<dim3(m->n_text_tiles, BH), dim3(256), 0, st>>>(
             kv.tpart_k, kv.tpart_v, m->d_text_tiles, m->n_partials, m->N, static_cast<T *>(kv.dk),
@@ -526,6 +736,9 @@ hipError_t launch_attn_bwd(const moc_meta *m, int BH, int d, int dtype, const vo
     KvArgs kv{};
     kv.q = q; kv.k = k; kv.v = v; kv.d_o = d_o;
     kv.lse = lse; kv.delta = a.delta;
+    kv.lse2 = reinterpret_cast<const float *>(ws + L.lse2);
+    kv.glse = reinterpret_cast<const float *>(ws + L.glse);
+    kv.gdelta = reinterpret_cast<const float *>(ws + L.gdelta);
     kv.dk = dk; kv.dv = dv;
     kv.tpart_k = reinterpret_cast<float *>(ws + L.tpart_k);
     kv.tpart_v = reinterpret_cast<float *>(ws + L.tpart_v);

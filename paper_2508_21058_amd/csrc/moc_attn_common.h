@@ -177,6 +177,77 @@ template <int D, int ROWS> struct TileLoader<D, bf16_t, ROWS> {
             }
         }
     }
+    // Gathered rows named by a wave-uniform list (entries = (row << 5) | slot).
+    // The list is read through scalar loads, which do not touch the vector-memory
+    // counter that the asynchronous tile loads are tracked with. ListRows holds
+    // this wave's rows of one tile; load it once, use it for every tensor.
+    // The loads and the wait for them are ONE asm statement: the compiler does
+    // not know that a scalar load completes later, so the results must be valid
+    // when the statement ends (outputs are early-clobber: the address registers
+    // of the later loads must stay intact while the earlier ones issue).
+    struct ListRows { int row[P]; };
+    __device__ __forceinline__ ListRows list_rows(const int32_t *entries, int valid) const {
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        static_assert(RPI == 4 || RPI == 8, "rows per instruction");
+        static_assert(P <= 4, "at most four wave instructions per tile and wave");
+        constexpr int NV = RPI / 4;
+        i32x4 ev[4][2];
+        int last;                                  // rows >= valid repeat the last valid row
+        const int32_t *p0 = entries + (valid - 1);
+        const int32_t *pv[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) pv[p] = entries + min(wave + 4 * p, NI - 1) * RPI;
+        if (NV == 1) {
+            asm volatile("s_load_dword %0, %5, 0x0\n"
+                         "s_load_dwordx4 %1, %6, 0x0\n"
+                         "s_load_dwordx4 %2, %7, 0x0\n"
+                         "s_load_dwordx4 %3, %8, 0x0\n"
+                         "s_load_dwordx4 %4, %9, 0x0\n"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&s"(last), "=&s"(ev[0][0]), "=&s"(ev[1][0]), "=&s"(ev[2][0]), "=&s"(ev[3][0])
+                         : "s"(p0), "s"(pv[0]), "s"(pv[1]), "s"(pv[2]), "s"(pv[3])
+                         : "memory");
+        } else {
+            asm volatile("s_load_dword %0, %9, 0x0\n"
+                         "s_load_dwordx4 %1, %10, 0x0\n"
+                         "s_load_dwordx4 %2, %10, 0x10\n"
+                         "s_load_dwordx4 %3, %11, 0x0\n"
+                         "s_load_dwordx4 %4, %11, 0x10\n"
+                         "s_load_dwordx4 %5, %12, 0x0\n"
+                         "s_load_dwordx4 %6, %12, 0x10\n"
+                         "s_load_dwordx4 %7, %13, 0x0\n"
+                         "s_load_dwordx4 %8, %13, 0x10\n"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&s"(last), "=&s"(ev[0][0]), "=&s"(ev[0][1]), "=&s"(ev[1][0]), "=&s"(ev[1][1]),
+                           "=&s"(ev[2][0]), "=&s"(ev[2][1]), "=&s"(ev[3][0]), "=&s"(ev[3][1])
+                         : "s"(p0), "s"(pv[0]), "s"(pv[1]), "s"(pv[2]), "s"(pv[3])
+                         : "memory");
+        }
+        ListRows r;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int n = wave + 4 * p;
+            int e = last;
+#pragma unroll
+            for (int j = 0; j < RPI; ++j) {
+                const int ej = n * RPI + j < valid ? ev[p][j / 4][j % 4] : last;
+                e = rlo == j ? ej : e;
+            }
+            r.row[p] = e >> 5;
+        }
+        return r;
+    }
+    __device__ __forceinline__ void issue_list(const bf16_t *base, const ListRows &lr, bf16_t *lds) const {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int n = wave + 4 * p;
+            if (NI % 4 == 0 || n < NI) {
+                const int row = n * RPI + rlo;
+                const int cg = cgp ^ SwTile<D>::sw(row);
+                dma(base + (size_t)lr.row[p] * D + cg * 8, lds + n * 512);
+            }
+        }
+    }
     // contiguous rows [0, valid) of a tile whose first row is at `tile` (a
     // wave-uniform pointer): scalar base + one 32-bit lane offset per load
     __device__ __forceinline__ void issue_rows(const bf16_t *tile, int valid, bf16_t *lds) const {
