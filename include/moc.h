@@ -25,7 +25,8 @@
  *   - Return value: MOC_OK (0) or a negative moc_status. Nothing throws, aborts
  *     or prints. All argument checks happen before any device work.
  *     moc_last_error() returns a thread-local detail string of the last failure.
- *   - d must be 64 or 128; 0 <= topk <= MOC_MAX_TOPK; N < 2^26; N * max(topk,1) < 2^31.
+ *   - d must be 64 or 128; 0 <= topk <= MOC_MAX_TOPK; N < 2^26; N * max(topk,1) < 2^31;
+ *     B * H * N * (topk + 1) < 2^31.
  */
 #ifndef MOC_H_
 #define MOC_H_

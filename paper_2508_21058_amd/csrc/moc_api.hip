@@ -39,6 +39,8 @@ int check_common(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int32_t 
     if (topk < 0 || topk > MOC_MAX_TOPK) return fail(MOC_ERR_SHAPE, "topk out of range [0, MOC_MAX_TOPK]");
     if ((long long)meta->N * std::max(topk, 1) >= (1LL << 31)) return fail(MOC_ERR_SHAPE, "N * topk must be < 2^31");
     if (meta->N >= (1 << 26)) return fail(MOC_ERR_SHAPE, "N must be < 2^26");
+    if ((long long)B * H * meta->N * (topk + 1) >= (1LL << 31))
+        return fail(MOC_ERR_SHAPE, "B * H * N * (topk + 1) must be < 2^31");
     if ((long long)B * H > 65535) return fail(MOC_ERR_SHAPE, "B * H must be <= 65535");
     return MOC_OK;
 }

@@ -178,17 +178,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(FwdArgs a) {
         if (!stage(IC<1>{})) break;
     }
 
-    if (!row_valid) return;
-    bf16_t *po = a.po + (((size_t)bh * N + qi) * a.slots + slot) * D;
-    const float sc = a.scale;
-#pragma unroll
-    for (int b = 0; b < DB; ++b)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int x = b * 32 + g * 8 + half * 4;
-            Io<bf16_t>::store4(po + x, dqacc[b][4 * g] * sc, dqacc[b][4 * g + 1] * sc, dqacc[b][4 * g + 2] * sc,
-                               dqacc[b][4 * g + 3] * sc);
-        }
+    __syncthreads();      // tile buffers are free: reuse them for the output transpose
+    const size_t prow = ((size_t)bh * N + qi) * a.slots + slot;
+    store_rows_bf16<D>(smem, wave, lane, dqacc, a.scale, row_valid ? (int)prow : -1, a.po);
 }
 
 template <int D, typename T>
@@ -203,15 +195,24 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const bf16_t *__restrict_
     const int slots = topk + 1;
     const size_t row = (size_t)bh * N + i;
     const int32_t *sr = sel + row * topk;
-    float acc[8], f[8];
-    Io<bf16_t>::load8f(part + (row * slots + topk) * D + c8 * 8, acc);
-    for (int s = 0; s < topk; ++s) {
-        const int j = sr[s];
-        if (j >= 0 && j < C) {
-            Io<bf16_t>::load8f(part + (row * slots + s) * D + c8 * 8, f);
+    float acc[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] += f[e];
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    const bf16_t *pbase = part + row * slots * D + c8 * 8;
+    for (int s0 = 0; s0 < slots; s0 += 4) {
+        float w[4], f[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int s = s0 + u;
+            bool ok = s == topk;
+            if (s < topk) { const int j = sr[s]; ok = j >= 0 && j < C; }
+            w[u] = ok ? 1.f : 0.f;
+            Io<bf16_t>::load8f(pbase + (size_t)(ok ? s : topk) * D, f[u]);
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(w[u], f[u][e], acc[e]);
     }
     Io<T>::store8(dq + row * D + c8 * 8, acc);
 }

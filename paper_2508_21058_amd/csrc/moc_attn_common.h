@@ -144,6 +144,45 @@ template <int D, typename T, int ROWS> struct RowStager {
     }
 };
 
+// Epilogue of the query-stationary passes. A transposed accumulator holds, per
+// lane, 4-feature pieces of ONE row; storing those directly scatters 8-byte
+// writes over 32 rows per instruction and the L2 writes partial lines back
+// several times. Instead every wave transposes its 32 x D tile through its own
+// 32 x (D + 4) bf16 patch of LDS and stores whole 16-byte groups, 16 lanes per
+// 256-byte row. `dst_row` is this lane's destination row index (in rows of D
+// bf16) or -1 if its row is not to be written; `scale` multiplies the values.
+// All waves of the workgroup must have finished reading `smem` (barrier before).
+template <int D>
+__device__ __forceinline__ void store_rows_bf16(char *smem, int wave, int lane, const f32x16 *acc, float scale,
+                                                int dst_row, bf16_t *out) {
+    constexpr int DB = D / 32, RS = D + 4;             // padded row: consecutive rows shift by 2 banks
+    const int half = lane >> 5, l32 = lane & 31;
+    bf16_t *patch = reinterpret_cast<bf16_t *>(smem) + wave * (32 * RS + 64);
+    int32_t *rowidx = reinterpret_cast<int32_t *>(patch + 32 * RS);
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            Io<bf16_t>::store4(patch + l32 * RS + b * 32 + g * 8 + half * 4, acc[b][4 * g] * scale,
+                               acc[b][4 * g + 1] * scale, acc[b][4 * g + 2] * scale, acc[b][4 * g + 3] * scale);
+    if (half == 0) rowidx[l32] = dst_row;
+    __builtin_amdgcn_wave_barrier();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    constexpr int LPR = D / 8, RPI = 64 / LPR;          // lanes per row, rows per instruction
+    const int cg = lane % LPR, r0 = lane / LPR;
+#pragma unroll
+    for (int it = 0; it < 32 / RPI; ++it) {
+        const int r = it * RPI + r0;
+        const int dr = rowidx[r];
+        const u32x2 lo2 = *reinterpret_cast<const u32x2 *>(patch + r * RS + cg * 8);
+        const u32x2 hi2 = *reinterpret_cast<const u32x2 *>(patch + r * RS + cg * 8 + 4);
+        if (dr >= 0) {
+            u32x4 v = {lo2[0], lo2[1], hi2[0], hi2[1]};
+            *reinterpret_cast<u32x4 *>(out + (size_t)dr * D + cg * 8) = v;
+        }
+    }
+}
+
 // Moves ROWS source rows of D features into a swizzled LDS tile (SwTile<D>).
 //   issue(base, rowfn, lds)  starts the transfer of a tile into `lds`
 //   commit(lds)              finishes it (before the barrier that publishes `lds`)

@@ -182,20 +182,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
         if (!stage(IC<1>{})) break;
     }
 
-    if (!row_valid) return;
+    __syncthreads();      // every wave is done with the tile buffers: reuse them for the output transpose
     const float l_tot = xhalf_sum(l_run);
     const float inv = 1.f / l_tot;
     const size_t prow = ((size_t)bh * N + qi) * a.slots + slot;
-    bf16_t *po = a.po + prow * D;
-#pragma unroll
-    for (int b = 0; b < DB; ++b)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int x = b * 32 + g * 8 + half * 4;
-            Io<bf16_t>::store4(po + x, oacc[b][4 * g] * inv, oacc[b][4 * g + 1] * inv, oacc[b][4 * g + 2] * inv,
-                               oacc[b][4 * g + 3] * inv);
-        }
-    if (half == 0) a.plse[prow] = m_run * a.scale + __logf(l_tot);
+    store_rows_bf16<D>(smem, wave, lane, oacc, inv, row_valid ? (int)prow : -1, a.po);
+    if (row_valid && half == 0) a.plse[prow] = m_run * a.scale + __logf(l_tot);
 }
 
 // o = sum_s exp(lse_s - lse) o_s over the forced-link slot and the used routed slots
@@ -224,21 +216,27 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(const bf16_t *__restrict
         if (j >= 0 && j < C) z += __expf(pl[s] - mx);
     }
     const float tot = mx + __logf(z);
-    float acc[8], f[8];
-    {
-        const float w = __expf(pl[topk] - tot);
-        Io<bf16_t>::load8f(po + (row * slots + topk) * D + c8 * 8, f);
+    // unused slots read the forced-link slot again with weight 0, so all loads
+    // are unconditional and several are in flight
+    float acc[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = w * f[e];
-    }
-    for (int s = 0; s < topk; ++s) {
-        const int j = sr[s];
-        if (j >= 0 && j < C) {
-            const float w = __expf(pl[s] - tot);
-            Io<bf16_t>::load8f(po + (row * slots + s) * D + c8 * 8, f);
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    const bf16_t *pbase = po + row * slots * D + c8 * 8;
+    for (int s0 = 0; s0 < slots; s0 += 4) {
+        float w[4], f[4][8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = fmaf(w, f[e], acc[e]);
+        for (int u = 0; u < 4; ++u) {
+            const int s = s0 + u;
+            bool ok = s == topk;
+            if (s < topk) { const int j = sr[s]; ok = j >= 0 && j < C; }
+            const int src = ok ? s : topk;
+            w[u] = ok ? __expf(pl[src] - tot) : 0.f;
+            Io<bf16_t>::load8f(pbase + (size_t)src * D, f[u]);
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(w[u], f[u][e], acc[e]);
     }
     Io<T>::store8(o + row * D + c8 * 8, acc);
     if (c8 == 0) lse[row] = tot;
