@@ -39,6 +39,8 @@ __global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ o, con
 #pragma unroll
     for (int w = TPQ / 2; w >= 1; w >>= 1) s += __shfl_xor(s, w, 64);
     if (row < rows && c8 == 0) { delta[row] = s; lse2[row] = lse[row] * kLog2e; }
+    // one slot past the end holds +inf: the lse2 of the padding rows of ragged query tiles
+    if (blockIdx.x == 0 && threadIdx.x == 0) lse2[rows] = INFINITY;
 }
 
 // ------------------------------------------------------------------ dQ pass
@@ -245,20 +247,27 @@ __device__ __forceinline__ void dkdv_block(const char *smem, LaneOffs<D> &lo, co
     lo.pin();
     f32x16 sacc, dpacc;
     {
-        bf16x8 qa[KS], da[KS];
+        // the dO fragments reuse the registers of the Q fragments as those are consumed
+        bf16x8 fr[KS];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) qa[s] = lo.template frag<QOFF + RB>(smem, s);
+        for (int s = 0; s < KS; ++s) fr[s] = lo.template frag<QOFF + RB>(smem, s);
+        sacc = zero16();
+        dpacc = zero16();
 #pragma unroll
-        for (int s = 0; s < KS; ++s) da[s] = lo.template frag<DOOFF + RB>(smem, s);
-        sacc = mfma32(qa[0], kf[0], zero16());
+        for (int s = 0; s < KS; ++s) {
+            sacc = mfma32(fr[s], kf[s], sacc);
+            fr[s] = lo.template frag<DOOFF + RB>(smem, s);
+        }
 #pragma unroll
-        for (int s = 1; s < KS; ++s) sacc = mfma32(qa[s], kf[s], sacc);
-        dpacc = mfma32(da[0], vf[0], zero16());
-#pragma unroll
-        for (int s = 1; s < KS; ++s) dpacc = mfma32(da[s], vf[s], dpacc);
+        for (int s = 0; s < KS; ++s) dpacc = mfma32(fr[s], vf[s], dpacc);
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-        for (int u = 0; u < 2 * KS - 4; ++u) {
+        for (int u = 0; u < KS - 4; ++u) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < KS; ++u) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
@@ -475,62 +484,146 @@ __global__ __launch_bounds__(256) void gather_stats_kernel(const int32_t *__rest
     gdelta[(size_t)bh * NK + pos] = delta[(size_t)bh * N + i];
 }
 
-// s_waitcnt that only bounds the number of outstanding vector-memory operations
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 64, "vmcnt range");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+// The two halves of the 8-wave key-stationary kernel, for one tile of 32 queries
+// and one block of 32 keys.
+//   score (waves 0-3): S = Q K^T and delta - dP = delta - dO V^T on the matrix
+//     cores (the V fragments are held negated and the accumulator starts at
+//     delta, read from LDS straight into the accumulator registers), then
+//     P = exp2(c S - lse2) and -dS = P (delta - dP); both leave through LDS as
+//     bf16 operand fragments (the register image acc_to_frag produces, one
+//     16-byte word per lane and 16-query step). Rows past the end of a ragged
+//     tile carry lse2 = +inf, so their P and dS come out as exact zeros.
+//   grad (waves 4-7): dV^T += dO^T P and -dK^T += Q^T (-dS) with the transposed
+//     tile reads; the lane that reads a fragment word is the lane that wrote it.
+//     The sign of dK is put right in the final scaling.
+// score is split into its matrix half and its vector half so that the caller
+// can run the matrix half of the next tile under the vector half of this one.
+// Per-stage statistics in LDS: for each group of 8 queries, 8 x lse2 then 8 x delta.
+template <int D, int QOFF, int DOOFF>
+__device__ __forceinline__ void score_mfma(const char *smem, const LaneOffs<D> &lo, const float *stats, const bf16x8 *kf,
+                                           const bf16x8 *nvf, f32x16 &sacc, f32x16 &dpacc, int lane) {
+    constexpr int KS = D / 16;
+    const int half = lane >> 5;
+    bf16x8 qa[KS], da[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qa[s] = lo.template frag<QOFF>(smem, s);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) da[s] = lo.template frag<DOOFF>(smem, s);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(stats + g * 16 + 8 + half * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dpacc[4 * g + e] = d4[e];
+    }
+    sacc = mfma32(qa[0], kf[0], zero16());
+    dpacc = mfma32(da[0], nvf[0], dpacc);
+#pragma unroll
+    for (int s = 1; s < KS; ++s) {
+        sacc = mfma32(qa[s], kf[s], sacc);
+        dpacc = mfma32(da[s], nvf[s], dpacc);
+    }
+}
+__device__ __forceinline__ void score_valu(const float *stats, f32x16 &sacc, f32x16 &dpacc, char *pds, float c,
+                                           int lane) {
+    const int half = lane >> 5;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4 *>(stats + g * 16 + half * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = 4 * g + e;
+            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, -l4[e]));
+            sacc[i] = p;
+            dpacc[i] *= p;
+        }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        *reinterpret_cast<bf16x8 *>(pds + ks * 1024) = acc_to_frag(sacc, ks);
+        *reinterpret_cast<bf16x8 *>(pds + (2 + ks) * 1024) = acc_to_frag(dpacc, ks);
+    }
 }
 
-// bf16 storage: the query stream of an item is mostly a gather of rows scattered
-// over the sequence, so one tile of look-ahead does not cover the memory
-// latency. This variant keeps NS - 1 tiles of asynchronous global->LDS loads in
-// flight: before tile t is consumed the wave waits only until its own loads of
-// tile t have landed (vmcnt bound, no drain), then one barrier publishes the tile
-// and frees the buffer of tile t-1 for the loads of tile t+NS-1. Everything the
-// loop loads, per-query lse and delta included, goes through the async path, so
-// no register-destination load forces an early wait.
+// transposed fragments of 16 queries (step KSTEP of a tile): dO^T and Q^T, all feature blocks
+template <int D> struct GradFrags { bf16x8 qt[D / 32], dot[D / 32]; };
+template <int D, int QOFF, int DOOFF, int KSTEP>
+__device__ __forceinline__ void grad_load(const char *smem, const LaneOffs<D> &lo, GradFrags<D> &f) {
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b) f.dot[b] = lo.template tfrag<DOOFF + KSTEP * 16 * D * 2>(smem, b);
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b) f.qt[b] = lo.template tfrag<QOFF + KSTEP * 16 * D * 2>(smem, b);
+}
 template <int D>
-__global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
+__device__ __forceinline__ void grad_mfma(const GradFrags<D> &f, const bf16x8 &pf, const bf16x8 &dsf, f32x16 *dkacc,
+                                          f32x16 *dvacc) {
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b) {
+        dvacc[b] = mfma32(f.dot[b], pf, dvacc[b]);
+        dkacc[b] = mfma32(f.qt[b], dsf, dkacc[b]);
+    }
+}
+
+// bf16 storage. Eight waves per workgroup, two per SIMD, in two roles: waves
+// 0-3 turn a query tile into P and dS for key blocks 0-3 (they hold the K and
+// V fragments and do all the exponentials), waves 4-7 hold the dK / dV
+// accumulators of the same key blocks, consume P and dS one step later, and
+// issue all the global->LDS copies. The matrix work is split evenly, no
+// contraction is done twice, each role fits the 256-register budget of two
+// resident waves, and on every SIMD the exponentials and LDS waits of one role
+// run under the matrix instructions of the other. A wave issues at most one
+// instruction every four cycles, so the loop is written for a low instruction
+// count per matrix instruction: inside a score wave the matrix instructions of
+// tile t+1 sit between the vector instructions of tile t, and the copy
+// addressing is kept to a few scalar and vector operations per tile.
+//
+// Step t (t = -1 .. ntiles), one workgroup barrier per step:
+//   score waves: matrix half on tile t+1, vector half on tile t -> P/dS buffer t&1
+//   grad waves : tile t-1 with P/dS buffer (t-1)&1
+// so tiles t-1 .. t+1 are resident and the stage of tile t-2 is free.
+// The query stream of an item is mostly a gather of rows scattered over the
+// sequence, so one tile of look-ahead does not cover the memory latency: the
+// remaining NS - 3 stages are asynchronous copies in flight. Before the barrier
+// of step t a grad wave waits only until its own copies of tile t+1 have landed
+// (vmcnt bound, no drain). Everything the loop loads, per-query lse and delta
+// included, goes through the async path, so no register-destination load
+// forces an early wait; the list words that name the gathered rows are scalar
+// loads issued one step before the copies that use them.
+template <int D>
+__global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
     typedef bf16_t T;
-    constexpr int BQ = 64, NS = 4;
+    constexpr int BQ = 32, NS = 7;
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int TB = BQ * D * 2;                 // bytes of one Q (or dO) tile
     constexpr int SB = 2 * TB;                     // bytes of one stage: Q tile, dO tile
-    constexpr int LPT = 2 * (BQ * D * 2 / 1024 / 4) + 2;   // async loads per wave and tile
+    constexpr int RPI = 512 / D;                   // tile rows per copy instruction (a wave moves 1 KB)
+    constexpr int NI = BQ / RPI;                   // copy instructions per tile and tensor
+    constexpr int PI = NI / 4;                     // ... per grad wave
+    constexpr int LPT = 2 * PI + 1;                // copies per grad wave and tile: Q, dO, lse/delta
+    static_assert(NI % 4 == 0, "tile rows must divide evenly among the four grad waves");
     __shared__ __attribute__((aligned(1024))) char smem[NS * SB];
-    __shared__ __attribute__((aligned(256))) float lse_s[NS][BQ], delta_s[NS][BQ];
+    // [tile parity][key block][P step 0, P step 1, dS step 0, dS step 1][lane] 16-byte fragment words
+    __shared__ __attribute__((aligned(1024))) char pds_s[2 * 4 * 4 * 1024];
+    __shared__ __attribute__((aligned(256))) float stats_s[NS][2 * BQ];
+    static_assert(NS * SB >= 4 * DB * 16 * 64 * 4, "accumulator exchange must fit the tile buffers");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
+    const bool grad_role = wave >= 4;
+    const int w4 = wave & 3;
     const int N = a.N;
     int logical;
     if (!xcd_remap((long long)a.n_items * a.BH, logical)) return;
     const int bh = logical / a.n_items;
     const KvItem item = a.items[logical - bh * a.n_items];
 
-    const T *qbase = static_cast<const T *>(a.q) + (size_t)bh * N * D;
-    const T *kbase = static_cast<const T *>(a.k) + (size_t)bh * N * D;
-    const T *vbase = static_cast<const T *>(a.v) + (size_t)bh * N * D;
-    const T *dobase = static_cast<const T *>(a.d_o) + (size_t)bh * N * D;
-    const float *lse2 = a.lse2 + (size_t)bh * N;
-    const float *delta = a.delta + (size_t)bh * N;
-
-    const bool split = item.key_len <= 32;         // see the register-staged variant
-    const int kblk = split ? 0 : wave;
+    // A tile of <= 32 keys (the ragged tail of a chunk) would leave three waves of
+    // each role idle: instead the four waves of a role take the same keys, split
+    // the query tiles among themselves and the accumulators are added at the end.
+    const bool split = item.key_len <= 32;
+    const int kblk = split ? 0 : w4;
     const int nk = min(32, item.key_len - kblk * 32);
     const bool wave_active = nk > 0;
     const int key = wave_active ? item.key_start + kblk * 32 + min(l32, nk - 1) : item.key_start;
-    bf16x8 kf[KS], vf[KS];
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        kf[s] = Io<T>::load8(kbase + (size_t)key * D + s * 16 + half * 8);
-        vf[s] = Io<T>::load8(vbase + (size_t)key * D + s * 16 + half * 8);
-    }
-    f32x16 dkacc[DB], dvacc[DB];
-#pragma unroll
-    for (int b = 0; b < DB; ++b) { dkacc[b] = zero16(); dvacc[b] = zero16(); }
-    LaneOffs<D> lo;
-    lo.init(lane);
 
     const int nA = (item.q_len + BQ - 1) / BQ;
     // all of these are plain values (never reassigned), so nothing of the loop state lives in memory
@@ -538,82 +631,256 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
     const int32_t *loff = a.list_off + (size_t)bh * (a.C + 1);
     const int lbeg = routed ? loff[item.chunk] : 0;
     const int cntB = routed ? loff[item.chunk + 1] - lbeg : 0;
-    const size_t lpos = (size_t)bh * N * a.topk + lbeg;
-    const int32_t *const entries = a.qlist + lpos;
-    const float *const glse = a.glse + lpos;
-    const float *const gdelta = a.gdelta + lpos;
     const int ntiles = nA + (cntB + BQ - 1) / BQ;
     if (ntiles == 0) return;
 
-    TileLoader<D, T, BQ> ld(tid);
-    auto tile_valid = [&](int t) { return t < nA ? min(BQ, item.q_len - t * BQ) : min(BQ, cntB - (t - nA) * BQ); };
-    // every wave issues exactly LPT async loads per tile
-    auto issue = [&](int t, int st) {
-        const int nv = tile_valid(t);
-        bf16_t *qdst = reinterpret_cast<bf16_t *>(smem + st * SB);
-        bf16_t *dodst = reinterpret_cast<bf16_t *>(smem + st * SB + TB);
-        const int r16 = min(wave * 16 + (lane & 15), nv - 1);    // this wave's 16 rows of the lse / delta vectors
-        const bool contig = t < nA;
-        const int q0 = item.q_start + t * BQ, g0 = (t - nA) * BQ;
-        if (contig) {
-            ld.issue_rows(qbase + (size_t)q0 * D, nv, qdst);
-            ld.issue_rows(dobase + (size_t)q0 * D, nv, dodst);
-        } else {
-            const auto lr = ld.list_rows(entries + g0, nv);
-            ld.issue_list(qbase, lr, qdst);
-            ld.issue_list(dobase, lr, dodst);
-        }
-        const float *lp = (contig ? lse2 + q0 : glse + g0) + r16;
-        const float *dp = (contig ? delta + q0 : gdelta + g0) + r16;
-        if (lane < 16) {
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)lp,
-                                             (__attribute__((address_space(3))) void *)(&lse_s[st][wave * 16]), 4, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)dp,
-                                             (__attribute__((address_space(3))) void *)(&delta_s[st][wave * 16]), 4, 0, 0);
-        }
-    };
-
-    const float c = a.scale_log2;
-    wait_vmcnt<0>();     // K / V fragments are in registers before the asynchronous stream starts
-#pragma unroll
-    for (int p = 0; p < NS - 1; ++p)
-        if (p < ntiles) issue(p, p);
-    for (int t = 0; t < ntiles; ++t) {
-        const int st = t % NS;
-        // tile t complete for this wave: at most the loads of the younger tiles may be outstanding
-        const int younger = min(NS - 2, ntiles - 1 - t);
-        if (younger >= 2) wait_vmcnt<2 * LPT>();
-        else if (younger == 1) wait_vmcnt<LPT>();
-        else wait_vmcnt<0>();
+    auto step_barrier = [&]() {
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        if (t + NS - 1 < ntiles) issue(t + NS - 1, (t + NS - 1) % NS);
-        const int nv = tile_valid(t);
-        LaneOffs<D> lc = lo;
+    };
+    auto next_stage = [&](int st) { return st == NS - 1 ? 0 : st + 1; };
+    LaneOffs<D> lo;
+    lo.init(lane);
+    char *const pds = pds_s + w4 * 4096 + lane * 16;
+    // split mode: the four waves of a role take the tiles round-robin
+    auto mine = [&](int t) { return wave_active && (!split || (t & 3) == w4); };
+    const bool fused = wave_active && !split;
+
+    f32x16 dkacc[DB], dvacc[DB];
+    if (!grad_role) {
+        // ------------------------------------------------------------ score waves
+        const T *kbase = static_cast<const T *>(a.k) + (size_t)bh * N * D;
+        const T *vbase = static_cast<const T *>(a.v) + (size_t)bh * N * D;
+        bf16x8 kf[KS], nvf[KS];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) lc.row[s] += st * SB;
+        for (int s = 0; s < KS; ++s) {
+            kf[s] = Io<T>::load8(kbase + (size_t)key * D + s * 16 + half * 8);
+            u32x4 v = __builtin_bit_cast(u32x4, Io<T>::load8(vbase + (size_t)key * D + s * 16 + half * 8));
 #pragma unroll
-        for (int u = 0; u < 2 * DB; ++u) lc.tr[u] += st * SB;
-        const bool mine = !split || (t & 1) == (wave >> 1);
-        const bool do0 = wave_active && mine && (!split || (wave & 1) == 0);
-        const bool do1 = wave_active && mine && nv > 32 && (!split || (wave & 1) == 1);
-        if (do0) dkdv_block<D, 0, TB, 0>(smem, lc, lse_s[st], delta_s[st], kf, vf, dkacc, dvacc, c, nv, lane);
-        if (do1) dkdv_block<D, 0, TB, 32>(smem, lc, lse_s[st], delta_s[st], kf, vf, dkacc, dvacc, c, nv, lane);
+            for (int e = 0; e < 4; ++e) v[e] ^= 0x80008000u;      // -V
+            nvf[s] = __builtin_bit_cast(bf16x8, v);
+        }
+        const float c = a.scale_log2;
+        auto at_stage = [&](int st) {      // row-operand offsets of a stage (too far apart for an instruction offset)
+            lo.pin();
+            LaneOffs<D> lc;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) lc.row[s] = lo.row[s] + st * SB;
+            return lc;
+        };
+        if (fused) {
+            // two accumulator sets take turns: while one goes through the vector half, the
+            // matrix half of the next tile fills the other
+            f32x16 sA, dpA, sB, dpB;
+            auto both = [&](f32x16 &s_nxt, f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, int st, int stn, int buf) {
+                score_mfma<D, 0, TB>(smem, at_stage(stn), stats_s[stn], kf, nvf, s_nxt, dp_nxt, lane);
+                score_valu(stats_s[st], s_cur, dp_cur, pds + (buf << 14), c, lane);
+                // a few tile reads ahead, then per matrix instruction one tile read and a share of the
+                // vector work of the previous tile
+                __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+                for (int u = 0; u < 2 * KS; ++u) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 64 / (2 * KS), 0);
+                }
+                wait_lgkm0();   // P / dS are in LDS before the next barrier publishes them
+            };
+            step_barrier();                                           // step -1
+            score_mfma<D, 0, TB>(smem, at_stage(0), stats_s[0], kf, nvf, sA, dpA, lane);
+            int st = 0, t = 0;      // st = stage of tile t; at the top of the loop set A holds tile t (t even)
+            while (true) {
+                step_barrier();                                       // step t, t even
+                if (t + 1 >= ntiles) { score_valu(stats_s[st], sA, dpA, pds, c, lane); wait_lgkm0(); break; }
+                const int st1 = next_stage(st);
+                both(sB, dpB, sA, dpA, st, st1, 0);
+                ++t;
+                step_barrier();                                       // step t, t odd
+                if (t + 1 >= ntiles) { score_valu(stats_s[st1], sB, dpB, pds + (1 << 14), c, lane); wait_lgkm0(); break; }
+                st = next_stage(st1);
+                both(sA, dpA, sB, dpB, st1, st, 1);
+                ++t;
+            }
+            step_barrier();                                           // step ntiles
+        } else {
+            int st = NS - 1;     // stage of tile t
+            for (int t = -1; t <= ntiles; ++t) {
+                step_barrier();
+                if (t >= 0 && t < ntiles && mine(t)) {
+                    f32x16 sacc, dpacc;
+                    score_mfma<D, 0, TB>(smem, at_stage(st), stats_s[st], kf, nvf, sacc, dpacc, lane);
+                    score_valu(stats_s[st], sacc, dpacc, pds + ((t & 1) << 14), c, lane);
+                    wait_lgkm0();
+                }
+                st = next_stage(st);
+            }
+        }
+    } else {
+        // ------------------------------------------------------------ grad waves
+        const char *qbase = static_cast<const char *>(a.q) + (size_t)bh * N * D * 2;
+        const char *dobase = static_cast<const char *>(a.d_o) + (size_t)bh * N * D * 2;
+        const float *lse2 = a.lse2 + (size_t)bh * N;
+        const float *delta = a.delta + (size_t)bh * N;
+        const float *const inf_slot = a.lse2 + (size_t)a.BH * N;    // holds +inf
+        const size_t lpos = (size_t)bh * N * a.topk + lbeg;
+        const int32_t *const entries = a.qlist + lpos;
+        const float *const glse = a.glse + lpos;
+        const float *const gdelta = a.gdelta + lpos;
+#pragma unroll
+        for (int b = 0; b < DB; ++b) dkacc[b] = zero16(), dvacc[b] = zero16();
+
+        // copy addressing: this wave's instruction p covers tile rows (w4 + 4p) * RPI + [0, RPI)
+        const int rlo = lane / (D / 8), cgp = lane % (D / 8);
+        int trow[PI];
+        uint32_t vcol[PI], voff[PI];
+#pragma unroll
+        for (int p = 0; p < PI; ++p) {
+            trow[p] = (w4 + 4 * p) * RPI + rlo;
+            vcol[p] = (uint32_t)((cgp ^ SwTile<D>::sw(trow[p])) * 16);
+            voff[p] = (uint32_t)(trow[p] * D * 2) + vcol[p];
+        }
+        const int srow = w4 * 8 + (lane & 7);          // this lane's query of the lse (lanes 0-7) / delta (8-15) copy
+        const bool s_lse = lane < 8;
+        const uint32_t smem_at = lds_address(smem), stats_at = lds_address(stats_s);
+        auto tile_valid = [&](int t) { return t < nA ? min(BQ, item.q_len - t * BQ) : min(BQ, cntB - (t - nA) * BQ); };
+        // list words of tile u (a gathered tile), wanted one step before issue(u)
+        int raw_last = 0, raw[PI][RPI];
+        auto fetch = [&](int u) {
+            if (u >= nA && u < ntiles) {
+                typedef const __attribute__((address_space(4))) int32_t *cptr;
+                cptr cp = (cptr)(uintptr_t)(entries + (u - nA) * BQ);
+                raw_last = cp[tile_valid(u) - 1];
+#pragma unroll
+                for (int p = 0; p < PI; ++p)
+#pragma unroll
+                    for (int j = 0; j < RPI; ++j) raw[p][j] = cp[(w4 + 4 * p) * RPI + j];
+            }
+        };
+        // LPT async copies per tile, tiles in order: ist is the stage of the next tile to be issued
+        int ist = 0;
+        auto issue = [&](int u) {
+            const uint32_t qat = smem_at + ist * SB + w4 * 1024, sat = stats_at + ist * (2 * BQ * 4) + w4 * 64;
+            ist = next_stage(ist);
+            const int nv = tile_valid(u);
+            const bool full = nv == BQ;
+            if (u < nA) {
+                const size_t q0 = (size_t)item.q_start + (size_t)u * BQ;
+                const char *qp = qbase + q0 * (D * 2), *dop = dobase + q0 * (D * 2);
+#pragma unroll
+                for (int p = 0; p < PI; ++p) {
+                    const uint32_t off = full ? voff[p] : (uint32_t)(min(trow[p], nv - 1) * D * 2) + vcol[p];
+                    async_copy16_at(qp, off, qat + p * 4096);
+                    async_copy16_at(dop, off, qat + TB + p * 4096);
+                }
+                const float *sp = (s_lse ? lse2 : delta) + q0 + (full ? srow : min(srow, nv - 1));
+                if (!full && s_lse && srow >= nv) sp = inf_slot;
+                if (lane < 16) async_copy4_at(sp, sat);
+            } else {
+                const int g0 = (u - nA) * BQ;
+#pragma unroll
+                for (int p = 0; p < PI; ++p) {
+                    int e = raw_last;
+#pragma unroll
+                    for (int j = 0; j < RPI; ++j) {
+                        const int ej = full || (w4 + 4 * p) * RPI + j < nv ? raw[p][j] : raw_last;
+                        e = (j == 0 || rlo == j) ? ej : e;
+                    }
+                    const size_t off = ((size_t)(uint32_t)(e >> 5) * (D * 2)) | vcol[p];
+                    async_copy16_at(qbase + off, qat + p * 4096);
+                    async_copy16_at(dobase + off, qat + TB + p * 4096);
+                }
+                const float *sp = (s_lse ? glse : gdelta) + g0 + (full ? srow : min(srow, nv - 1));
+                if (!full && s_lse && srow >= nv) sp = inf_slot;
+                if (lane < 16) async_copy4_at(sp, sat);
+            }
+        };
+        // own copies of tile u landed: at most the copies of the younger tiles may be outstanding
+        auto wait_tile = [&](int u) {
+            const int younger = min(NS - 4, ntiles - 1 - u);
+            static_assert(NS - 4 == 3, "cases below");
+            if (younger >= 3) wait_vmcnt<3 * LPT>();
+            else if (younger == 2) wait_vmcnt<2 * LPT>();
+            else if (younger == 1) wait_vmcnt<LPT>();
+            else wait_vmcnt<0>();
+        };
+        auto step_sync = [&](int t) {
+            if (t + 1 < ntiles) wait_tile(t + 1);
+            step_barrier();
+            if (t + NS - 2 < ntiles) issue(t + NS - 2);
+            fetch(t + NS - 1);
+        };
+#pragma unroll
+        for (int p = 0; p <= NS - 4; ++p)
+            if (p < ntiles) { fetch(p); issue(p); }
+        fetch(NS - 3);
+
+        auto at_stage = [&](int st) {
+            lo.pin();
+            LaneOffs<D> lc;
+#pragma unroll
+            for (int u = 0; u < 2 * DB; ++u) lc.tr[u] = lo.tr[u] + st * SB;
+            return lc;
+        };
+        if (fused) {
+            // the fragments of the first 16 queries of a tile are read one step early, while
+            // the workgroup is still on its way to the barrier that publishes the tile's P / dS
+            GradFrags<D> f0, f1;
+            step_sync(-1);
+            step_sync(0);
+            grad_load<D, 0, TB, 0>(smem, at_stage(0), f0);
+            int st = 0;      // stage of tile t - 1
+            for (int t = 1; t <= ntiles; ++t) {
+                step_sync(t);
+                const char *pp = pds + (((t - 1) & 1) << 14);
+                const bf16x8 pf0 = *reinterpret_cast<const bf16x8 *>(pp);
+                const bf16x8 dsf0 = *reinterpret_cast<const bf16x8 *>(pp + 2048);
+                const bf16x8 pf1 = *reinterpret_cast<const bf16x8 *>(pp + 1024);
+                const bf16x8 dsf1 = *reinterpret_cast<const bf16x8 *>(pp + 3072);
+                grad_load<D, 0, TB, 1>(smem, at_stage(st), f1);
+                grad_mfma<D>(f0, pf0, dsf0, dkacc, dvacc);
+                // next tile (the last step reads the same tile again: the values are not used)
+                const int stn = t < ntiles ? next_stage(st) : st;
+                grad_load<D, 0, TB, 0>(smem, at_stage(stn), f0);
+                grad_mfma<D>(f1, pf1, dsf1, dkacc, dvacc);
+                st = stn;
+            }
+        } else {
+            int st = NS - 2;     // stage of tile t - 1
+            for (int t = -1; t <= ntiles; ++t) {
+                step_sync(t);
+                if (t >= 1 && mine(t - 1)) {
+                    const char *pp = pds + (((t - 1) & 1) << 14);
+                    const LaneOffs<D> lc = at_stage(st);
+                    GradFrags<D> f;
+                    grad_load<D, 0, TB, 0>(smem, lc, f);
+                    grad_mfma<D>(f, *reinterpret_cast<const bf16x8 *>(pp), *reinterpret_cast<const bf16x8 *>(pp + 2048),
+                                 dkacc, dvacc);
+                    grad_load<D, 0, TB, 1>(smem, lc, f);
+                    grad_mfma<D>(f, *reinterpret_cast<const bf16x8 *>(pp + 1024),
+                                 *reinterpret_cast<const bf16x8 *>(pp + 3072), dkacc, dvacc);
+                }
+                st = next_stage(st);
+            }
+        }
     }
 
     if (split) {
+        // the four gradient waves hold partial sums for the same keys in the same
+        // register layout: exchange them through LDS (16 KB per wave and tensor), wave 4 adds
         float *xch = reinterpret_cast<float *>(smem);
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             f32x16 *acc = pass == 0 ? dkacc : dvacc;
             __syncthreads();
+            if (grad_role) {
 #pragma unroll
-            for (int b = 0; b < DB; ++b)
+                for (int b = 0; b < DB; ++b)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) xch[((wave * DB + b) * 16 + i) * 64 + lane] = acc[b][i];
+                    for (int i = 0; i < 16; ++i) xch[((w4 * DB + b) * 16 + i) * 64 + lane] = acc[b][i];
+            }
             __syncthreads();
-            if (wave == 0) {
+            if (wave == 4) {
 #pragma unroll
                 for (int b = 0; b < DB; ++b)
 #pragma unroll
@@ -625,33 +892,33 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
                     }
             }
         }
-        if (wave != 0) return;
+        if (wave != 4) return;
     }
-    if (!wave_active || l32 >= nk) return;
-    const float sc = a.scale;
+    if (!grad_role || !wave_active || l32 >= nk) return;
+    const float dks = -a.scale;       // the accumulator holds -dK
     if (item.partial < 0) {
-        T *dk = static_cast<T *>(a.dk) + ((size_t)bh * N + key) * D;
-        T *dv = static_cast<T *>(a.dv) + ((size_t)bh * N + key) * D;
+        T *dkp = static_cast<T *>(a.dk) + ((size_t)bh * N + key) * D;
+        T *dvp = static_cast<T *>(a.dv) + ((size_t)bh * N + key) * D;
 #pragma unroll
         for (int b = 0; b < DB; ++b)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int x = b * 32 + g * 8 + half * 4;
-                Io<T>::store4(dk + x, dkacc[b][4 * g] * sc, dkacc[b][4 * g + 1] * sc, dkacc[b][4 * g + 2] * sc,
-                              dkacc[b][4 * g + 3] * sc);
-                Io<T>::store4(dv + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
+                Io<T>::store4(dkp + x, dkacc[b][4 * g] * dks, dkacc[b][4 * g + 1] * dks, dkacc[b][4 * g + 2] * dks,
+                              dkacc[b][4 * g + 3] * dks);
+                Io<T>::store4(dvp + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
             }
     } else {
         const size_t prow = ((size_t)bh * a.n_partials + item.partial) * kKeyTile + kblk * 32 + l32;
-        float *pk = a.tpart_k + prow * D, *pv = a.tpart_v + prow * D;
+        float *dkp = a.tpart_k + prow * D, *dvp = a.tpart_v + prow * D;
 #pragma unroll
         for (int b = 0; b < DB; ++b)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int x = b * 32 + g * 8 + half * 4;
-                Io<float>::store4(pk + x, dkacc[b][4 * g] * sc, dkacc[b][4 * g + 1] * sc, dkacc[b][4 * g + 2] * sc,
-                                  dkacc[b][4 * g + 3] * sc);
-                Io<float>::store4(pv + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
+                Io<float>::store4(dkp + x, dkacc[b][4 * g] * dks, dkacc[b][4 * g + 1] * dks, dkacc[b][4 * g + 2] * dks,
+                                  dkacc[b][4 * g + 3] * dks);
+                Io<float>::store4(dvp + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
             }
     }
 }
@@ -696,7 +963,7 @@ static hipError_t bwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, KvArgs &kv
                 kv.qlist, kv.list_off, m->N, NK, m->C, kv.lse2, kv.delta, const_cast<float *>(kv.glse),
                 const_cast<float *>(kv.gdelta));
         }
-        attn_bwd_dkdv_pipe_kernel<D><<<dim3(xcd_grid((long long)m->n_kvitems * BH)), dim3(256), 0, st>>>(kv);
+        attn_bwd_dkdv_pipe_kernel<D><<<dim3(xcd_grid((long long)m->n_kvitems * BH)), dim3(512), 0, st>>>(kv);
     } else
         attn_bwd_dkdv_kernel<D, T><<<dim3(xcd_grid((long long)m->n_kvitems * BH)), dim3(256), 0, st>>>(kv); }
     if (m->n_text_tiles > 0) { MOC_PROF("text_reduce", st);

@@ -191,29 +191,30 @@ __device__ __forceinline__ void store_rows_bf16(char *smem, int wave, int lane, 
 // of LDS, lane l writing bytes [16 l, 16 l + 16), so each lane fetches the
 // global element that belongs at its swizzled LDS position.
 // fp32 storage needs a conversion, so it goes through registers.
-template <int D, typename T, int ROWS> struct TileLoader;
+template <int D, typename T, int ROWS, int NW = 4> struct TileLoader;   // NW = waves that share the loads
 
-template <int D, int ROWS> struct TileLoader<D, bf16_t, ROWS> {
+template <int D, int ROWS, int NW> struct TileLoader<D, bf16_t, ROWS, NW> {
     static constexpr int RPI = 512 / D;                 // rows per wave instruction
     static constexpr int NI = ROWS / RPI;               // wave instructions per tile
-    static constexpr int P = (NI + 3) / 4;              // per wave (4 waves)
+    static constexpr int P = (NI + NW - 1) / NW;        // per wave
+    // With fewer instructions than waves the surplus waves repeat the loads of the
+    // first ones (same source, same destination): every wave then issues the same
+    // number of loads per tile, which is what a bounded vmcnt wait counts on.
+    static constexpr bool kRepeat = NI < NW;
+    static_assert(kRepeat ? NW % NI == 0 : NI % NW == 0, "tile rows must divide evenly among the waves");
     int wave, rlo, cgp;
+    __device__ __forceinline__ int slot(int p) const { return kRepeat ? wave % NI : wave + NW * p; }
     __device__ __forceinline__ explicit TileLoader(int tid)
         : wave(__builtin_amdgcn_readfirstlane(tid >> 6)), rlo((tid & 63) / (D / 8)), cgp((tid & 63) % (D / 8)) {}
-    static __device__ __forceinline__ void dma(const bf16_t *g, bf16_t *lds) {
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                         (__attribute__((address_space(3))) void *)lds, 16, 0, 0);
-    }
+    static __device__ __forceinline__ void dma(const bf16_t *g, bf16_t *lds) { async_copy16(g, lds); }
     // arbitrary (gathered) rows: rowfn(r) is the global row of tile row r
     template <typename F> __device__ __forceinline__ void issue(const bf16_t *base, F rowfn, bf16_t *lds) const {
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const int n = wave + 4 * p;
-            if (NI % 4 == 0 || n < NI) {
-                const int row = n * RPI + rlo;
-                const int cg = cgp ^ SwTile<D>::sw(row);
-                dma(base + (size_t)rowfn(row) * D + cg * 8, lds + n * 512);
-            }
+            const int n = slot(p);
+            const int row = n * RPI + rlo;
+            const int cg = cgp ^ SwTile<D>::sw(row);
+            dma(base + (size_t)rowfn(row) * D + cg * 8, lds + n * 512);
         }
     }
     // Gathered rows named by a wave-uniform list (entries = (row << 5) | slot).
@@ -225,6 +226,35 @@ template <int D, int ROWS> struct TileLoader<D, bf16_t, ROWS> {
     // when the statement ends (outputs are early-clobber: the address registers
     // of the later loads must stay intact while the earlier ones issue).
     struct ListRows { int row[P]; };
+    // The same in two steps, for callers that want the list words a step ahead of
+    // the copies that use them: fetch_list() reads this wave's words of a tile with
+    // ordinary loads from the constant address space (wave-uniform address, so they
+    // are scalar loads the compiler tracks itself), select_rows() turns them into
+    // the lane's row once they are needed. Only for one instruction per wave (P == 1).
+    struct ListRaw { int last; int e[RPI]; };
+    __device__ __forceinline__ ListRaw fetch_list(const int32_t *entries, int valid) const {
+        static_assert(P == 1, "one wave instruction per tile");
+        typedef const __attribute__((address_space(4))) int32_t *cptr;
+        cptr c = (cptr)(uintptr_t)entries;
+        ListRaw r;
+        r.last = c[valid - 1];
+        const int n = slot(0);
+#pragma unroll
+        for (int j = 0; j < RPI; ++j) r.e[j] = c[n * RPI + j];
+        return r;
+    }
+    __device__ __forceinline__ ListRows select_rows(const ListRaw &raw, int valid) const {
+        const int n = slot(0);
+        int e = raw.last;
+#pragma unroll
+        for (int j = 0; j < RPI; ++j) {
+            const int ej = n * RPI + j < valid ? raw.e[j] : raw.last;
+            e = rlo == j ? ej : e;
+        }
+        ListRows r;
+        r.row[0] = e >> 5;
+        return r;
+    }
     __device__ __forceinline__ ListRows list_rows(const int32_t *entries, int valid) const {
         typedef int i32x4 __attribute__((ext_vector_type(4)));
         static_assert(RPI == 4 || RPI == 8, "rows per instruction");
@@ -235,8 +265,23 @@ template <int D, int ROWS> struct TileLoader<D, bf16_t, ROWS> {
         const int32_t *p0 = entries + (valid - 1);
         const int32_t *pv[4];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) pv[p] = entries + min(wave + 4 * p, NI - 1) * RPI;
-        if (NV == 1) {
+        for (int p = 0; p < 4; ++p) pv[p] = entries + (p < P ? slot(p) : slot(P - 1)) * RPI;
+        if (P == 1 && NV == 1) {
+            asm volatile("s_load_dword %0, %2, 0x0\n"
+                         "s_load_dwordx4 %1, %3, 0x0\n"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&s"(last), "=&s"(ev[0][0])
+                         : "s"(p0), "s"(pv[0])
+                         : "memory");
+        } else if (P == 1) {
+            asm volatile("s_load_dword %0, %3, 0x0\n"
+                         "s_load_dwordx4 %1, %4, 0x0\n"
+                         "s_load_dwordx4 %2, %4, 0x10\n"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&s"(last), "=&s"(ev[0][0]), "=&s"(ev[0][1])
+                         : "s"(p0), "s"(pv[0])
+                         : "memory");
+        } else if (NV == 1) {
             asm volatile("s_load_dword %0, %5, 0x0\n"
                          "s_load_dwordx4 %1, %6, 0x0\n"
                          "s_load_dwordx4 %2, %7, 0x0\n"
@@ -265,7 +310,7 @@ template <int D, int ROWS> struct TileLoader<D, bf16_t, ROWS> {
         ListRows r;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const int n = wave + 4 * p;
+            const int n = slot(p);
             int e = last;
 #pragma unroll
             for (int j = 0; j < RPI; ++j) {
@@ -279,12 +324,10 @@ template <int D, int ROWS> struct TileLoader<D, bf16_t, ROWS> {
     __device__ __forceinline__ void issue_list(const bf16_t *base, const ListRows &lr, bf16_t *lds) const {
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const int n = wave + 4 * p;
-            if (NI % 4 == 0 || n < NI) {
-                const int row = n * RPI + rlo;
-                const int cg = cgp ^ SwTile<D>::sw(row);
-                dma(base + (size_t)lr.row[p] * D + cg * 8, lds + n * 512);
-            }
+            const int n = slot(p);
+            const int row = n * RPI + rlo;
+            const int cg = cgp ^ SwTile<D>::sw(row);
+            dma(base + (size_t)lr.row[p] * D + cg * 8, lds + n * 512);
         }
     }
     // contiguous rows [0, valid) of a tile whose first row is at `tile` (a
@@ -292,19 +335,18 @@ template <int D, int ROWS> struct TileLoader<D, bf16_t, ROWS> {
     __device__ __forceinline__ void issue_rows(const bf16_t *tile, int valid, bf16_t *lds) const {
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const int n = wave + 4 * p;
-            if (NI % 4 == 0 || n < NI) {
-                const int row = n * RPI + rlo;
-                const int cg = cgp ^ SwTile<D>::sw(row);
-                const uint32_t off = (uint32_t)(min(row, valid - 1) * D + cg * 8) * 2u;
-                dma(reinterpret_cast<const bf16_t *>(reinterpret_cast<const char *>(tile) + off), lds + n * 512);
-            }
+            const int n = slot(p);
+            const int row = n * RPI + rlo;
+            const int cg = cgp ^ SwTile<D>::sw(row);
+            const uint32_t off = (uint32_t)(min(row, valid - 1) * D + cg * 8) * 2u;
+            async_copy16(tile, off, lds + n * 512);
         }
     }
-    __device__ __forceinline__ void commit(bf16_t *) const {}
+    // the tile is complete once this wave's copies have landed (and the workgroup has met at a barrier)
+    __device__ __forceinline__ void commit(bf16_t *) const { wait_vmcnt<0>(); }
 };
 
-template <int D, int ROWS> struct TileLoader<D, float, ROWS> {
+template <int D, int ROWS> struct TileLoader<D, float, ROWS, 4> {
     RowStager<D, float, ROWS> st;
     __device__ __forceinline__ explicit TileLoader(int tid) : st(tid) {}
     template <typename F> __device__ __forceinline__ void issue(const float *base, F rowfn, bf16_t *) {

@@ -216,6 +216,53 @@ template <int D> struct LaneOffs {
     }
 };
 
+// s_waitcnt that only bounds the number of outstanding vector-memory operations
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+// s_waitcnt that only waits for the wave's LDS (and scalar-memory) operations
+__device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+// Asynchronous global -> LDS copies (global_load_lds): every lane moves BYTES
+// bytes from its own global address to LDS address  base + lane * BYTES, where
+// base is wave-uniform (it travels in M0). The copy completes out of sight of
+// the wave; it counts in vmcnt like any vector-memory load.
+// They are written as inline assembly on purpose. Given the intrinsic, the
+// compiler treats every later LDS read as depending on the newest copy and
+// puts an s_waitcnt vmcnt(0) in front of it, which drains the very prefetch
+// the copy was issued for. Issued this way the compiler does not know about
+// them, so the CALLER orders them: wait_vmcnt<N>() (N = copies this wave has
+// issued since the ones it needs) and then a workgroup barrier before any lane
+// reads what other waves copied.
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)p;
+}
+__device__ __forceinline__ void async_copy16(const void *g, void *lds) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(g), "s"(lds_address(lds)) : "memory", "m0");
+}
+// wave-uniform base pointer + 32-bit unsigned byte offset per lane
+__device__ __forceinline__ void async_copy16(const void *base, uint32_t off, void *lds) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(off), "s"(base), "s"(lds_address(lds)) : "memory", "m0");
+}
+// the same with the LDS destination given as an address (see lds_address)
+__device__ __forceinline__ void async_copy16_at(const void *g, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(g), "s"(lds) : "memory", "m0");
+}
+__device__ __forceinline__ void async_copy16_at(const void *base, uint32_t off, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(off), "s"(base), "s"(lds) : "memory", "m0");
+}
+__device__ __forceinline__ void async_copy4_at(const void *g, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" :: "v"(g), "s"(lds) : "memory", "m0");
+}
+__device__ __forceinline__ void async_copy4(const void *g, void *lds) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :: "v"(g), "s"(lds_address(lds)) : "memory", "m0");
+}
+
 // max (or sum) of a value with its counterpart in the other half-wave, in all
 // lanes, without going through LDS (v_permlane32_swap)
 __device__ __forceinline__ float xhalf_max(float v) {

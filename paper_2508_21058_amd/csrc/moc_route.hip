@@ -195,10 +195,11 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
             x = fminf(tv[p], x);
             tv[p] = hi;
         }
-        if (more) __syncthreads();
+        if (more) { ld.commit(nullptr); __syncthreads(); }
         return more;
     };
     issue(0, 0);
+    ld.commit(nullptr);
     __syncthreads();
     for (int t = 0;;) {
         if (!pass1(IC<0>{}, t++)) break;
@@ -244,11 +245,12 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
                 ++cnt;
             }
         }
-        if (more) __syncthreads();
+        if (more) { ld.commit(nullptr); __syncthreads(); }
         return more;
     };
     __syncthreads();
     issue(0, 0);
+    ld.commit(nullptr);
     __syncthreads();
     for (int t = 0;;) {
         if (!pass2(IC<0>{}, t++)) break;
