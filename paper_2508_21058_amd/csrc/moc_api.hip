@@ -95,9 +95,8 @@ AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd)
     L.po = take((size_t)BH * N * slots * d * 2);
     if (with_bwd) {
         L.delta = take((size_t)BH * N * 4);
-        L.lse2 = take(((size_t)BH * N + 1) * 4);     // + one slot holding +inf
-        L.glse = take((size_t)BH * N * std::max(topk, 1) * 4);
-        L.gdelta = take((size_t)BH * N * std::max(topk, 1) * 4);
+        L.stats2 = take(((size_t)BH * N + 1) * 8);     // (lse2, delta) pairs + one pair holding (+inf, 0)
+        L.gstats2 = take((size_t)BH * N * std::max(topk, 1) * 8);
         L.tpart_k = take((size_t)BH * m->n_partials * kKeyTile * d * 4);
         L.tpart_v = take((size_t)BH * m->n_partials * kKeyTile * d * 4);
     }

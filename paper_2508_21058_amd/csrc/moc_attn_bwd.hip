@@ -24,7 +24,7 @@ namespace moc {
 template <int D, typename T>
 __global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ o, const T *__restrict__ d_o, size_t rows,
                                                     const float *__restrict__ lse, float *__restrict__ delta,
-                                                    float *__restrict__ lse2) {
+                                                    float *__restrict__ stats2) {
     constexpr int TPQ = D / 8, QPW = 256 / TPQ;
     const size_t row = (size_t)blockIdx.x * QPW + threadIdx.x / TPQ;
     const int c8 = threadIdx.x % TPQ;
@@ -38,9 +38,14 @@ __global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ o, con
     }
 #pragma unroll
     for (int w = TPQ / 2; w >= 1; w >>= 1) s += __shfl_xor(s, w, 64);
-    if (row < rows && c8 == 0) { delta[row] = s; lse2[row] = lse[row] * kLog2e; }
-    // one slot past the end holds +inf: the lse2 of the padding rows of ragged query tiles
-    if (blockIdx.x == 0 && threadIdx.x == 0) lse2[rows] = INFINITY;
+    // stats2 holds per query the pair (lse * log2(e), delta) the key-stationary pass works with
+    if (row < rows && c8 == 0) {
+        delta[row] = s;
+        stats2[2 * row] = lse[row] * kLog2e;
+        stats2[2 * row + 1] = s;
+    }
+    // one pair past the end holds lse2 = +inf: the padding rows of ragged query tiles
+    if (blockIdx.x == 0 && threadIdx.x == 0) { stats2[2 * rows] = INFINITY; stats2[2 * rows + 1] = 0.f; }
 }
 
 // ------------------------------------------------------------------ dQ pass
@@ -222,8 +227,9 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const bf16_t *__restrict_
 // ------------------------------------------------------------------ dK/dV pass
 struct KvArgs {
     const void *q, *k, *v, *d_o;
-    const float *lse, *delta, *lse2;   // lse2 = lse * log2(e)
-    const float *glse, *gdelta;        // lse2 / delta gathered in the order of the inverse lists
+    const float *lse, *delta;
+    const float *stats2;               // per query (lse * log2(e), delta); one extra pair (+inf, 0) at the end
+    const float *gstats2;              // the same pairs gathered in the order of the inverse lists
     void *dk, *dv;
     float *tpart_k, *tpart_v;
     const KvItem *items;
@@ -469,19 +475,17 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkdv_kernel(KvArgs a) {
     }
 }
 
-// lse2 and delta of the queries of every inverse list, in list order, so the
+// (lse2, delta) of the queries of every inverse list, in list order, so the
 // key-stationary pass reads them as contiguous vectors
 __global__ __launch_bounds__(256) void gather_stats_kernel(const int32_t *__restrict__ qlist,
                                                            const int32_t *__restrict__ list_off, int N, int NK, int C,
-                                                           const float *__restrict__ lse2,
-                                                           const float *__restrict__ delta, float *__restrict__ glse,
-                                                           float *__restrict__ gdelta) {
+                                                           const float2 *__restrict__ stats2,
+                                                           float2 *__restrict__ gstats2) {
     const int bh = blockIdx.y;
     const int pos = blockIdx.x * 256 + threadIdx.x;
     if (pos >= list_off[(size_t)bh * (C + 1) + C]) return;
     const int i = qlist[(size_t)bh * NK + pos] >> 5;
-    glse[(size_t)bh * NK + pos] = lse2[(size_t)bh * N + i];
-    gdelta[(size_t)bh * NK + pos] = delta[(size_t)bh * N + i];
+    gstats2[(size_t)bh * NK + pos] = stats2[(size_t)bh * N + i];
 }
 
 // The two halves of the 8-wave key-stationary kernel, for one tile of 32 queries
@@ -598,12 +602,15 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
     constexpr int RPI = 512 / D;                   // tile rows per copy instruction (a wave moves 1 KB)
     constexpr int NI = BQ / RPI;                   // copy instructions per tile and tensor
     constexpr int PI = NI / 4;                     // ... per grad wave
-    constexpr int LPT = 2 * PI + 1;                // copies per grad wave and tile: Q, dO, lse/delta
+    constexpr int LPT = 2 * PI + 2;                // copies per grad wave and tile: list words, Q, dO, lse/delta
     static_assert(NI % 4 == 0, "tile rows must divide evenly among the four grad waves");
     __shared__ __attribute__((aligned(1024))) char smem[NS * SB];
     // [tile parity][key block][P step 0, P step 1, dS step 0, dS step 1][lane] 16-byte fragment words
     __shared__ __attribute__((aligned(1024))) char pds_s[2 * 4 * 4 * 1024];
     __shared__ __attribute__((aligned(256))) float stats_s[NS][2 * BQ];
+    // list words ((query << 5) | slot) of the gathered tiles about to be copied: [tile & 7][grad wave][8]
+    __shared__ __attribute__((aligned(128))) int32_t ent_s[8][BQ];
+    static_assert(PI * RPI == 8, "a grad wave copies 8 rows per tensor and tile");
     static_assert(NS * SB >= 4 * DB * 16 * 64 * 4, "accumulator exchange must fit the tile buffers");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -720,79 +727,94 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
         // ------------------------------------------------------------ grad waves
         const char *qbase = static_cast<const char *>(a.q) + (size_t)bh * N * D * 2;
         const char *dobase = static_cast<const char *>(a.d_o) + (size_t)bh * N * D * 2;
-        const float *lse2 = a.lse2 + (size_t)bh * N;
-        const float *delta = a.delta + (size_t)bh * N;
-        const float *const inf_slot = a.lse2 + (size_t)a.BH * N;    // holds +inf
+        const float *const inf_slot = a.stats2 + (size_t)a.BH * N * 2;   // the pair (+inf, 0)
         const size_t lpos = (size_t)bh * N * a.topk + lbeg;
         const int32_t *const entries = a.qlist + lpos;
-        const float *const glse = a.glse + lpos;
-        const float *const gdelta = a.gdelta + lpos;
 #pragma unroll
         for (int b = 0; b < DB; ++b) dkacc[b] = zero16(), dvacc[b] = zero16();
 
-        // copy addressing: this wave's instruction p covers tile rows (w4 + 4p) * RPI + [0, RPI)
+        // ---- copy addressing. This wave's copy p of a tensor covers tile rows (w4 + 4p) * RPI + [0, RPI).
+        // Per tile ("group") a wave issues, in this order: the list words of the tile four groups
+        // ahead (into a small LDS ring; a dummy copy when that tile is not a gathered one), PI copies
+        // of Q, PI of dO, one of lse2 / delta: LPT in all, always, so that a vmcnt bound counts groups.
+        // By the time a gathered tile's copies are issued its list words have landed: they are older
+        // than the three groups that may still be in flight.
         const int rlo = lane / (D / 8), cgp = lane % (D / 8);
-        int trow[PI];
         uint32_t vcol[PI], voff[PI];
+        auto trow = [&](int p) { return (w4 + 4 * p) * RPI + rlo; };
 #pragma unroll
         for (int p = 0; p < PI; ++p) {
-            trow[p] = (w4 + 4 * p) * RPI + rlo;
-            vcol[p] = (uint32_t)((cgp ^ SwTile<D>::sw(trow[p])) * 16);
-            voff[p] = (uint32_t)(trow[p] * D * 2) + vcol[p];
+            vcol[p] = (uint32_t)((cgp ^ SwTile<D>::sw(trow(p))) * 16);
+            voff[p] = (uint32_t)(trow(p) * D * 2) + vcol[p];
         }
-        const int srow = w4 * 8 + (lane & 7);          // this lane's query of the lse (lanes 0-7) / delta (8-15) copy
-        const bool s_lse = lane < 8;
-        const uint32_t smem_at = lds_address(smem), stats_at = lds_address(stats_s);
+        // lanes 0-7 copy lse2, lanes 8-15 delta, of the wave's 8 queries of a tile (pairs in memory)
+        const uint32_t soff = (uint32_t)(((w4 * 8 + (lane & 7)) * 2 + ((lane >> 3) & 1)) * 4);
+        const float *stc = a.stats2 + ((size_t)bh * N + item.q_start) * 2;    // next contiguous tile
+        const float *stg = a.gstats2 + lpos * 2;                              // next gathered tile
+        const uint32_t smem_at = lds_address(smem), stats_at = lds_address(stats_s), ent_at = lds_address(ent_s);
+        const uint32_t ent_rd = ent_at + w4 * 32 + rlo * 4;
         auto tile_valid = [&](int t) { return t < nA ? min(BQ, item.q_len - t * BQ) : min(BQ, cntB - (t - nA) * BQ); };
-        // list words of tile u (a gathered tile), wanted one step before issue(u)
-        int raw_last = 0, raw[PI][RPI];
-        auto fetch = [&](int u) {
-            if (u >= nA && u < ntiles) {
-                typedef const __attribute__((address_space(4))) int32_t *cptr;
-                cptr cp = (cptr)(uintptr_t)(entries + (u - nA) * BQ);
-                raw_last = cp[tile_valid(u) - 1];
-#pragma unroll
-                for (int p = 0; p < PI; ++p)
-#pragma unroll
-                    for (int j = 0; j < RPI; ++j) raw[p][j] = cp[(w4 + 4 * p) * RPI + j];
+        auto issue_words = [&](int v) {       // list words of tile v -> ring slot v & 7
+            const uint32_t dst = ent_at + (v & 7) * 128 + w4 * 32;
+            if (lane < 8) {
+                if (v >= nA && v < ntiles) {
+                    const int nvv = min(BQ, cntB - (v - nA) * BQ);
+                    const int eidx = (w4 + 4 * ((lane & 7) / RPI)) * RPI + (lane & 7) % RPI;
+                    async_copy4_at(entries + (v - nA) * BQ, (uint32_t)(min(eidx, nvv - 1) * 4), dst);
+                } else {
+                    async_copy4_at(inf_slot, 0u, dst);
+                }
             }
         };
-        // LPT async copies per tile, tiles in order: ist is the stage of the next tile to be issued
-        int ist = 0;
-        auto issue = [&](int u) {
+        int ist = 0;                          // stage of the next tile to be issued (tiles go out in order)
+        const char *qp = qbase + (size_t)item.q_start * (D * 2), *dop = dobase + (size_t)item.q_start * (D * 2);
+        auto issue_group = [&](int u) {
+            issue_words(u + 4);
             const uint32_t qat = smem_at + ist * SB + w4 * 1024, sat = stats_at + ist * (2 * BQ * 4) + w4 * 64;
             ist = next_stage(ist);
             const int nv = tile_valid(u);
-            const bool full = nv == BQ;
-            if (u < nA) {
-                const size_t q0 = (size_t)item.q_start + (size_t)u * BQ;
-                const char *qp = qbase + q0 * (D * 2), *dop = dobase + q0 * (D * 2);
+            // (plain selects: a pointer picked and advanced inside the branches ends up in scratch memory)
+            const bool contig = u < nA;
+            const float *const st2 = contig ? stc : stg;
+            stc += contig ? BQ * 2 : 0;
+            stg += contig ? 0 : BQ * 2;
+            if (contig) {
+                if (nv == BQ) {
 #pragma unroll
-                for (int p = 0; p < PI; ++p) {
-                    const uint32_t off = full ? voff[p] : (uint32_t)(min(trow[p], nv - 1) * D * 2) + vcol[p];
-                    async_copy16_at(qp, off, qat + p * 4096);
-                    async_copy16_at(dop, off, qat + TB + p * 4096);
-                }
-                const float *sp = (s_lse ? lse2 : delta) + q0 + (full ? srow : min(srow, nv - 1));
-                if (!full && s_lse && srow >= nv) sp = inf_slot;
-                if (lane < 16) async_copy4_at(sp, sat);
-            } else {
-                const int g0 = (u - nA) * BQ;
-#pragma unroll
-                for (int p = 0; p < PI; ++p) {
-                    int e = raw_last;
-#pragma unroll
-                    for (int j = 0; j < RPI; ++j) {
-                        const int ej = full || (w4 + 4 * p) * RPI + j < nv ? raw[p][j] : raw_last;
-                        e = (j == 0 || rlo == j) ? ej : e;
+                    for (int p = 0; p < PI; ++p) {
+                        async_copy16_at(qp, voff[p], qat + p * 4096);
+                        async_copy16_at(dop, voff[p], qat + TB + p * 4096);
                     }
+                } else {
+#pragma unroll
+                    for (int p = 0; p < PI; ++p) {
+                        const uint32_t off = (uint32_t)(min(trow(p), nv - 1) * D * 2) + vcol[p];
+                        async_copy16_at(qp, off, qat + p * 4096);
+                        async_copy16_at(dop, off, qat + TB + p * 4096);
+                    }
+                }
+                qp += BQ * D * 2;
+                dop += BQ * D * 2;
+            } else {
+#pragma unroll
+                for (int p = 0; p < PI; ++p) {
+                    const int e = *reinterpret_cast<const __attribute__((address_space(3))) int *>(
+                        (uintptr_t)(ent_rd + (u & 7) * 128 + p * RPI * 4));
                     const size_t off = ((size_t)(uint32_t)(e >> 5) * (D * 2)) | vcol[p];
                     async_copy16_at(qbase + off, qat + p * 4096);
                     async_copy16_at(dobase + off, qat + TB + p * 4096);
                 }
-                const float *sp = (s_lse ? glse : gdelta) + g0 + (full ? srow : min(srow, nv - 1));
-                if (!full && s_lse && srow >= nv) sp = inf_slot;
-                if (lane < 16) async_copy4_at(sp, sat);
+            }
+            if (lane < 16) {
+                if (nv == BQ) {
+                    async_copy4_at(st2, soff, sat);
+                } else {
+                    // ragged tile: rows past the end take lse2 = +inf and the delta of the last row
+                    const int srow = w4 * 8 + (lane & 7);
+                    const float *sp = st2 + min(srow, nv - 1) * 2 + ((lane >> 3) & 1);
+                    if (lane < 8 && srow >= nv) sp = inf_slot;
+                    async_copy4_at(sp, sat);
+                }
             }
         };
         // own copies of tile u landed: at most the copies of the younger tiles may be outstanding
@@ -804,16 +826,22 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
             else if (younger == 1) wait_vmcnt<LPT>();
             else wait_vmcnt<0>();
         };
-        auto step_sync = [&](int t) {
+        auto step_wait = [&](int t) {
             if (t + 1 < ntiles) wait_tile(t + 1);
             step_barrier();
-            if (t + NS - 2 < ntiles) issue(t + NS - 2);
-            fetch(t + NS - 1);
         };
+        auto step_issue = [&](int t) {
+            if (t + NS - 2 < ntiles) issue_group(t + NS - 2);
+        };
+        // the list words of the first four tiles go ahead of everything (needed only if one of them is gathered)
+        if (nA < 4) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) issue_words(v);
+            wait_vmcnt<0>();
+        }
 #pragma unroll
         for (int p = 0; p <= NS - 4; ++p)
-            if (p < ntiles) { fetch(p); issue(p); }
-        fetch(NS - 3);
+            if (p < ntiles) issue_group(p);
 
         auto at_stage = [&](int st) {
             lo.pin();
@@ -824,14 +852,17 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
         };
         if (fused) {
             // the fragments of the first 16 queries of a tile are read one step early, while
-            // the workgroup is still on its way to the barrier that publishes the tile's P / dS
+            // the workgroup is still on its way to the barrier that publishes the tile's P / dS;
+            // the copies of a step go out between the two halves of its matrix work
             GradFrags<D> f0, f1;
-            step_sync(-1);
-            step_sync(0);
+            step_wait(-1);
+            step_issue(-1);
+            step_wait(0);
+            step_issue(0);
             grad_load<D, 0, TB, 0>(smem, at_stage(0), f0);
             int st = 0;      // stage of tile t - 1
             for (int t = 1; t <= ntiles; ++t) {
-                step_sync(t);
+                step_wait(t);
                 const char *pp = pds + (((t - 1) & 1) << 14);
                 const bf16x8 pf0 = *reinterpret_cast<const bf16x8 *>(pp);
                 const bf16x8 dsf0 = *reinterpret_cast<const bf16x8 *>(pp + 2048);
@@ -839,6 +870,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
                 const bf16x8 dsf1 = *reinterpret_cast<const bf16x8 *>(pp + 3072);
                 grad_load<D, 0, TB, 1>(smem, at_stage(st), f1);
                 grad_mfma<D>(f0, pf0, dsf0, dkacc, dvacc);
+                step_issue(t);
                 // next tile (the last step reads the same tile again: the values are not used)
                 const int stn = t < ntiles ? next_stage(st) : st;
                 grad_load<D, 0, TB, 0>(smem, at_stage(stn), f0);
@@ -848,7 +880,8 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
         } else {
             int st = NS - 2;     // stage of tile t - 1
             for (int t = -1; t <= ntiles; ++t) {
-                step_sync(t);
+                step_wait(t);
+                step_issue(t);
                 if (t >= 1 && mine(t - 1)) {
                     const char *pp = pds + (((t - 1) & 1) << 14);
                     const LaneOffs<D> lc = at_stage(st);
@@ -954,14 +987,14 @@ static hipError_t bwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, KvArgs &kv
     { MOC_PROF("delta", st);
     delta_kernel<D, T><<<dim3((unsigned)((rows + QPW - 1) / QPW)), dim3(256), 0, st>>>(
         static_cast<const T *>(o), static_cast<const T *>(a.d_o), rows, a.lse, const_cast<float *>(a.delta),
-        const_cast<float *>(kv.lse2)); }
+        const_cast<float *>(kv.stats2)); }
     { MOC_PROF("attn_bwd_dkdv", st);
     if constexpr (sizeof(T) == 2) {
         if (a.topk > 0) {
             const int NK = m->N * a.topk;
             gather_stats_kernel<<<dim3((NK + 255) / 256, BH), dim3(256), 0, st>>>(
-                kv.qlist, kv.list_off, m->N, NK, m->C, kv.lse2, kv.delta, const_cast<float *>(kv.glse),
-                const_cast<float *>(kv.gdelta));
+                kv.qlist, kv.list_off, m->N, NK, m->C, reinterpret_cast<const float2 *>(kv.stats2),
+                reinterpret_cast<float2 *>(const_cast<float *>(kv.gstats2)));
         }
         attn_bwd_dkdv_pipe_kernel<D><<<dim3(xcd_grid((long long)m->n_kvitems * BH)), dim3(512), 0, st>>>(kv);
     } else
@@ -1004,9 +1037,8 @@ hipError_t launch_attn_bwd(const moc_meta *m, int BH, int d, int dtype, const vo
     KvArgs kv{};
     kv.q = q; kv.k = k; kv.v = v; kv.d_o = d_o;
     kv.lse = lse; kv.delta = a.delta;
-    kv.lse2 = reinterpret_cast<const float *>(ws + L.lse2);
-    kv.glse = reinterpret_cast<const float *>(ws + L.glse);
-    kv.gdelta = reinterpret_cast<const float *>(ws + L.gdelta);
+    kv.stats2 = reinterpret_cast<const float *>(ws + L.stats2);
+    kv.gstats2 = reinterpret_cast<const float *>(ws + L.gstats2);
     kv.dk = dk; kv.dv = dv;
     kv.tpart_k = reinterpret_cast<float *>(ws + L.tpart_k);
     kv.tpart_v = reinterpret_cast<float *>(ws + L.tpart_v);

@@ -235,6 +235,12 @@ __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F
 // them, so the CALLER orders them: wait_vmcnt<N>() (N = copies this wave has
 // issued since the ones it needs) and then a workgroup barrier before any lane
 // reads what other waves copied.
+// a pointer the caller knows to be wave-uniform, in scalar registers whatever the compiler's analysis says
+__device__ __forceinline__ const void *uniform_ptr(const void *p) {
+    const uint64_t b = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    return (const void *)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ uint32_t lds_address(const void *p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)p;
 }
@@ -253,10 +259,14 @@ __device__ __forceinline__ void async_copy16_at(const void *g, uint32_t lds) {
 }
 __device__ __forceinline__ void async_copy16_at(const void *base, uint32_t off, uint32_t lds) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(off), "s"(base), "s"(lds) : "memory", "m0");
+                 :: "v"(off), "s"(uniform_ptr(base)), "s"(lds) : "memory", "m0");
 }
 __device__ __forceinline__ void async_copy4_at(const void *g, uint32_t lds) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" :: "v"(g), "s"(lds) : "memory", "m0");
+}
+__device__ __forceinline__ void async_copy4_at(const void *base, uint32_t off, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :: "v"(off), "s"(uniform_ptr(base)), "s"(lds) : "memory", "m0");
 }
 __device__ __forceinline__ void async_copy4(const void *g, void *lds) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"

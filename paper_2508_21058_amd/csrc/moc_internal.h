@@ -70,7 +70,7 @@ struct ProfScope {
 
 // Layout of the attention workspace (byte offsets); shared by fwd and bwd.
 struct AttnWs {
-    size_t cnt, list_off, tile_off, cursor, qlist, plse, po, delta, lse2, glse, gdelta, tpart_k, tpart_v, total;
+    size_t cnt, list_off, tile_off, cursor, qlist, plse, po, delta, stats2, gstats2, tpart_k, tpart_v, total;
 };
 AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd);
 
