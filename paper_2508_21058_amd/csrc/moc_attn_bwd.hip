@@ -548,6 +548,52 @@ __device__ __forceinline__ void score_valu(const float *stats, f32x16 &sacc, f32
     }
 }
 
+// One steady-state step of a score wave: the matrix half of the next tile
+// (accumulators s_nxt, dp_nxt; tile at the offsets lo_n, statistics stats_n)
+// written out between the vector half of the current one (s_cur, dp_cur,
+// stats_c). The order below is the order of issue: scheduling barriers keep
+// the compiler from regrouping it into a matrix phase and a vector phase,
+// which would leave the matrix pipe idle for the whole vector phase.
+template <int D, int QOFF, int DOOFF>
+__device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &lo_n, const float *stats_n,
+                                           const float *stats_c, const bf16x8 *kf, const bf16x8 *nvf, f32x16 &s_nxt,
+                                           f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, char *pds, float c, int lane) {
+    constexpr int KS = D / 16, EPS = 16 / KS;      // vector elements handled per contraction step
+    const int half = lane >> 5;
+    bf16x8 qa[KS], da[KS];
+    f32x4 l4[4];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        qa[s] = lo_n.template frag<QOFF>(smem, s);
+        da[s] = lo_n.template frag<DOOFF>(smem, s);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(stats_n + g * 16 + 8 + half * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dp_nxt[4 * g + e] = d4[e];
+        l4[g] = *reinterpret_cast<const f32x4 *>(stats_c + g * 16 + half * 4);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        s_nxt = mfma32(qa[s], kf[s], s == 0 ? zero16() : s_nxt);
+        dp_nxt = mfma32(da[s], nvf[s], dp_nxt);
+#pragma unroll
+        for (int i = s * EPS; i < (s + 1) * EPS; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s_cur[i], c, -l4[i >> 2][i & 3]));
+            s_cur[i] = p;
+            dp_cur[i] *= p;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        *reinterpret_cast<bf16x8 *>(pds + ks * 1024) = acc_to_frag(s_cur, ks);
+        *reinterpret_cast<bf16x8 *>(pds + (2 + ks) * 1024) = acc_to_frag(dp_cur, ks);
+    }
+}
+
 // transposed fragments of 16 queries (step KSTEP of a tile): dO^T and Q^T, all feature blocks
 template <int D> struct GradFrags { bf16x8 qt[D / 32], dot[D / 32]; };
 template <int D, int QOFF, int DOOFF, int KSTEP>
@@ -678,37 +724,35 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
         };
         if (fused) {
             // two accumulator sets take turns: while one goes through the vector half, the
-            // matrix half of the next tile fills the other
+            // matrix half of the next tile fills the other (no copies: the loop body is two steps)
             f32x16 sA, dpA, sB, dpB;
             auto both = [&](f32x16 &s_nxt, f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, int st, int stn, int buf) {
-                score_mfma<D, 0, TB>(smem, at_stage(stn), stats_s[stn], kf, nvf, s_nxt, dp_nxt, lane);
-                score_valu(stats_s[st], s_cur, dp_cur, pds + (buf << 14), c, lane);
-                // a few tile reads ahead, then per matrix instruction one tile read and a share of the
-                // vector work of the previous tile
-                __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-                for (int u = 0; u < 2 * KS; ++u) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 64 / (2 * KS), 0);
-                }
+                score_step<D, 0, TB>(smem, at_stage(stn), stats_s[stn], stats_s[st], kf, nvf, s_nxt, dp_nxt, s_cur,
+                                     dp_cur, pds + (buf << 14), c, lane);
                 wait_lgkm0();   // P / dS are in LDS before the next barrier publishes them
             };
             step_barrier();                                           // step -1
             score_mfma<D, 0, TB>(smem, at_stage(0), stats_s[0], kf, nvf, sA, dpA, lane);
-            int st = 0, t = 0;      // st = stage of tile t; at the top of the loop set A holds tile t (t even)
-            while (true) {
-                step_barrier();                                       // step t, t even
-                if (t + 1 >= ntiles) { score_valu(stats_s[st], sA, dpA, pds, c, lane); wait_lgkm0(); break; }
-                const int st1 = next_stage(st);
+            int st = 0, t = 0;      // st = stage of tile t; set A holds tile t (t even)
+            for (; t + 2 < ntiles; t += 2) {
+                const int st1 = next_stage(st), st2 = next_stage(st1);
+                step_barrier();                                       // step t
                 both(sB, dpB, sA, dpA, st, st1, 0);
-                ++t;
-                step_barrier();                                       // step t, t odd
-                if (t + 1 >= ntiles) { score_valu(stats_s[st1], sB, dpB, pds + (1 << 14), c, lane); wait_lgkm0(); break; }
-                st = next_stage(st1);
-                both(sA, dpA, sB, dpB, st1, st, 1);
-                ++t;
+                step_barrier();                                       // step t + 1
+                both(sA, dpA, sB, dpB, st1, st2, 1);
+                st = st2;
             }
+            if (t + 1 < ntiles) {                                     // two tiles left
+                const int st1 = next_stage(st);
+                step_barrier();
+                both(sB, dpB, sA, dpA, st, st1, 0);
+                step_barrier();
+                score_valu(stats_s[st1], sB, dpB, pds + (1 << 14), c, lane);
+            } else {                                                  // one tile left
+                step_barrier();
+                score_valu(stats_s[st], sA, dpA, pds, c, lane);
+            }
+            wait_lgkm0();
             step_barrier();                                           // step ntiles
         } else {
             int st = NS - 1;     // stage of tile t
