@@ -498,7 +498,7 @@ __global__ __launch_bounds__(256) void gather_stats_kernel(const int32_t *__rest
 //     16-byte word per lane and 16-query step). Rows past the end of a ragged
 //     tile carry lse2 = +inf, so their P and dS come out as exact zeros.
 //   grad (waves 4-7): dV^T += dO^T P and -dK^T += Q^T (-dS) with the transposed
-//     tile reads; the lane that reads a fragment word is the lane that wrote it.
+//     tile reads; a fragment word is read by the lane number that wrote it.
 //     The sign of dK is put right in the final scaling.
 // score is split into its matrix half and its vector half so that the caller
 // can run the matrix half of the next tile under the vector half of this one.
@@ -594,30 +594,11 @@ __device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &
     }
 }
 
-// transposed fragments of 16 queries (step KSTEP of a tile): dO^T and Q^T, all feature blocks
-template <int D> struct GradFrags { bf16x8 qt[D / 32], dot[D / 32]; };
-template <int D, int QOFF, int DOOFF, int KSTEP>
-__device__ __forceinline__ void grad_load(const char *smem, const LaneOffs<D> &lo, GradFrags<D> &f) {
-#pragma unroll
-    for (int b = 0; b < D / 32; ++b) f.dot[b] = lo.template tfrag<DOOFF + KSTEP * 16 * D * 2>(smem, b);
-#pragma unroll
-    for (int b = 0; b < D / 32; ++b) f.qt[b] = lo.template tfrag<QOFF + KSTEP * 16 * D * 2>(smem, b);
-}
-template <int D>
-__device__ __forceinline__ void grad_mfma(const GradFrags<D> &f, const bf16x8 &pf, const bf16x8 &dsf, f32x16 *dkacc,
-                                          f32x16 *dvacc) {
-#pragma unroll
-    for (int b = 0; b < D / 32; ++b) {
-        dvacc[b] = mfma32(f.dot[b], pf, dvacc[b]);
-        dkacc[b] = mfma32(f.qt[b], dsf, dkacc[b]);
-    }
-}
-
 // bf16 storage. Eight waves per workgroup, two per SIMD, in two roles: waves
 // 0-3 turn a query tile into P and dS for key blocks 0-3 (they hold the K and
 // V fragments and do all the exponentials), waves 4-7 hold the dK / dV
-// accumulators of the same key blocks, consume P and dS one step later, and
-// issue all the global->LDS copies. The matrix work is split evenly, no
+// accumulators (one block of 32 features each, for all key blocks), consume P
+// and dS one step later, and issue all the global->LDS copies. The matrix work is split evenly, no
 // contraction is done twice, each role fits the 256-register budget of two
 // resident waves, and on every SIMD the exponentials and LDS waits of one role
 // run under the matrix instructions of the other. A wave issues at most one
@@ -657,7 +638,6 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
     // list words ((query << 5) | slot) of the gathered tiles about to be copied: [tile & 7][grad wave][8]
     __shared__ __attribute__((aligned(128))) int32_t ent_s[8][BQ];
     static_assert(PI * RPI == 8, "a grad wave copies 8 rows per tensor and tile");
-    static_assert(NS * SB >= 4 * DB * 16 * 64 * 4, "accumulator exchange must fit the tile buffers");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
@@ -669,9 +649,9 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
     const int bh = logical / a.n_items;
     const KvItem item = a.items[logical - bh * a.n_items];
 
-    // A tile of <= 32 keys (the ragged tail of a chunk) would leave three waves of
-    // each role idle: instead the four waves of a role take the same keys, split
-    // the query tiles among themselves and the accumulators are added at the end.
+    // A tile of <= 32 keys (the ragged tail of a chunk) would leave three score waves
+    // idle: instead the four take the same keys and the query tiles round-robin, each
+    // writing its P / dS into its own key-block slot (the grad waves share every tile anyway).
     const bool split = item.key_len <= 32;
     const int kblk = split ? 0 : w4;
     const int nk = min(32, item.key_len - kblk * 32);
@@ -700,7 +680,6 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
     auto mine = [&](int t) { return wave_active && (!split || (t & 3) == w4); };
     const bool fused = wave_active && !split;
 
-    f32x16 dkacc[DB], dvacc[DB];
     if (!grad_role) {
         // ------------------------------------------------------------ score waves
         const T *kbase = static_cast<const T *>(a.k) + (size_t)bh * N * D;
@@ -774,8 +753,6 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
         const float *const inf_slot = a.stats2 + (size_t)a.BH * N * 2;   // the pair (+inf, 0)
         const size_t lpos = (size_t)bh * N * a.topk + lbeg;
         const int32_t *const entries = a.qlist + lpos;
-#pragma unroll
-        for (int b = 0; b < DB; ++b) dkacc[b] = zero16(), dvacc[b] = zero16();
 
         // ---- copy addressing. This wave's copy p of a tensor covers tile rows (w4 + 4p) * RPI + [0, RPI).
         // Per tile ("group") a wave issues, in this order: the list words of the tile four groups
@@ -887,116 +864,123 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
         for (int p = 0; p <= NS - 4; ++p)
             if (p < ntiles) issue_group(p);
 
-        auto at_stage = [&](int st) {
-            lo.pin();
-            LaneOffs<D> lc;
+        // ---- matrix work. A grad wave owns one block of 32 features (rows of dK^T / dV^T) for
+        // KPW key blocks: the transposed Q / dO fragments it reads from a tile are then shared by
+        // all its key blocks (a wave that owned a key block would read the whole tile, four times
+        // the transposed reads, and those run at half the rate of the plain 16-byte reads that
+        // fetch P and dS instead). With a single key block (split mode) the four waves still
+        // share every tile, one feature block each.
+        constexpr int DBW = DB < 4 ? DB : 4;       // feature blocks across the waves
+        constexpr int KPW = DBW;                   // key blocks per wave (4 waves cover DBW x (4 / DBW) x KPW blocks)
+        const int db = w4 % DBW, kg = w4 / DBW;
+        const int nkb = split ? 1 : (item.key_len + 31) / 32;                  // key blocks of the item
+        const int nmine = max(0, min(KPW, nkb - kg * KPW));                    // ... of this wave
+        f32x16 dk[KPW], dv[KPW];
 #pragma unroll
-            for (int u = 0; u < 2 * DB; ++u) lc.tr[u] = lo.tr[u] + st * SB;
-            return lc;
+        for (int j = 0; j < KPW; ++j) dk[j] = zero16(), dv[j] = zero16();
+        // lane offsets of the transposed reads of feature block db (see LaneOffs::init), 16-query step 0
+        int tr0, tr1;
+        {
+            const int i = lane & 15, bq = (lane >> 4) & 1;
+            const int x = 32 * db + 16 * bq + 4 * (i & 3), r0 = 4 * half + (i >> 2);
+            tr0 = (SwTile<D>::off(r0, x >> 3) + (x & 7)) * 2;
+            tr1 = (SwTile<D>::off(r0 + 8, x >> 3) + (x & 7)) * 2;
+        }
+        struct TFrags { bf16x8 qt[2], dot[2]; };   // Q^T and dO^T of the wave's features, both 16-query steps
+        auto tload = [&](int st) {
+            asm volatile("" : "+v"(tr0), "+v"(tr1));     // keep the stage base out of loop-invariant copies
+            typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+            typedef short s16x8 __attribute__((ext_vector_type(8)));
+            const char *base = smem + st * SB;
+            TFrags f;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int w = 0; w < 2; ++w) {
+                    const char *pt = base + w * TB + ks * 16 * D * 2;
+                    const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(pt + tr0));
+                    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(pt + tr1));
+                    const s16x8 r = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+                    (w == 0 ? f.qt[ks] : f.dot[ks]) = __builtin_bit_cast(bf16x8, r);
+                }
+            return f;
         };
-        if (fused) {
-            // the fragments of the first 16 queries of a tile are read one step early, while
-            // the workgroup is still on its way to the barrier that publishes the tile's P / dS;
-            // the copies of a step go out between the two halves of its matrix work
-            GradFrags<D> f0, f1;
-            step_wait(-1);
-            step_issue(-1);
-            step_wait(0);
-            step_issue(0);
-            grad_load<D, 0, TB, 0>(smem, at_stage(0), f0);
-            int st = 0;      // stage of tile t - 1
+        const char *const pds_rd = pds_s + lane * 16;
+        // tile u with fragments f: P / dS of key block slot kb0 + j feed accumulator j
+        auto gmfma = [&](const TFrags &f, int u, int j) {
+            const int kb0 = split ? (u & 3) : kg * KPW;
+            const char *pp = pds_rd + ((u & 1) << 14) + (kb0 + j) * 4096;
+            const bf16x8 pf0 = *reinterpret_cast<const bf16x8 *>(pp);
+            const bf16x8 pf1 = *reinterpret_cast<const bf16x8 *>(pp + 1024);
+            const bf16x8 dsf0 = *reinterpret_cast<const bf16x8 *>(pp + 2048);
+            const bf16x8 dsf1 = *reinterpret_cast<const bf16x8 *>(pp + 3072);
+            dv[j] = mfma32(f.dot[0], pf0, dv[j]);
+            dk[j] = mfma32(f.qt[0], dsf0, dk[j]);
+            dv[j] = mfma32(f.dot[1], pf1, dv[j]);
+            dk[j] = mfma32(f.qt[1], dsf1, dk[j]);
+        };
+        // The transposed fragments of a tile are read one step early, while the workgroup is
+        // still on its way to the barrier that publishes the tile's P / dS; the copies of a
+        // step go out in the middle of its matrix work.
+        step_wait(-1);
+        step_issue(-1);
+        step_wait(0);
+        step_issue(0);
+        TFrags f = tload(0);
+        int st = 0;      // stage of tile t - 1
+        if (nmine == KPW) {
             for (int t = 1; t <= ntiles; ++t) {
                 step_wait(t);
-                const char *pp = pds + (((t - 1) & 1) << 14);
-                const bf16x8 pf0 = *reinterpret_cast<const bf16x8 *>(pp);
-                const bf16x8 dsf0 = *reinterpret_cast<const bf16x8 *>(pp + 2048);
-                const bf16x8 pf1 = *reinterpret_cast<const bf16x8 *>(pp + 1024);
-                const bf16x8 dsf1 = *reinterpret_cast<const bf16x8 *>(pp + 3072);
-                grad_load<D, 0, TB, 1>(smem, at_stage(st), f1);
-                grad_mfma<D>(f0, pf0, dsf0, dkacc, dvacc);
+#pragma unroll
+                for (int j = 0; j < KPW / 2; ++j) gmfma(f, t - 1, j);
                 step_issue(t);
+#pragma unroll
+                for (int j = KPW / 2; j < KPW; ++j) gmfma(f, t - 1, j);
                 // next tile (the last step reads the same tile again: the values are not used)
-                const int stn = t < ntiles ? next_stage(st) : st;
-                grad_load<D, 0, TB, 0>(smem, at_stage(stn), f0);
-                grad_mfma<D>(f1, pf1, dsf1, dkacc, dvacc);
-                st = stn;
+                st = t < ntiles ? next_stage(st) : st;
+                f = tload(st);
             }
         } else {
-            int st = NS - 2;     // stage of tile t - 1
-            for (int t = -1; t <= ntiles; ++t) {
+            for (int t = 1; t <= ntiles; ++t) {
                 step_wait(t);
                 step_issue(t);
-                if (t >= 1 && mine(t - 1)) {
-                    const char *pp = pds + (((t - 1) & 1) << 14);
-                    const LaneOffs<D> lc = at_stage(st);
-                    GradFrags<D> f;
-                    grad_load<D, 0, TB, 0>(smem, lc, f);
-                    grad_mfma<D>(f, *reinterpret_cast<const bf16x8 *>(pp), *reinterpret_cast<const bf16x8 *>(pp + 2048),
-                                 dkacc, dvacc);
-                    grad_load<D, 0, TB, 1>(smem, lc, f);
-                    grad_mfma<D>(f, *reinterpret_cast<const bf16x8 *>(pp + 1024),
-                                 *reinterpret_cast<const bf16x8 *>(pp + 3072), dkacc, dvacc);
-                }
-                st = next_stage(st);
+#pragma unroll
+                for (int j = 0; j < KPW; ++j)
+                    if (j < nmine) gmfma(f, t - 1, j);
+                st = t < ntiles ? next_stage(st) : st;
+                f = tload(st);
             }
         }
-    }
 
-    if (split) {
-        // the four gradient waves hold partial sums for the same keys in the same
-        // register layout: exchange them through LDS (16 KB per wave and tensor), wave 4 adds
-        float *xch = reinterpret_cast<float *>(smem);
+        // ---- results: lane = key, registers = the wave's 32 features; the accumulator holds -dK
+        const float dks = -a.scale;
 #pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
-            f32x16 *acc = pass == 0 ? dkacc : dvacc;
-            __syncthreads();
-            if (grad_role) {
+        for (int j = 0; j < KPW; ++j) {
+            if (j >= nmine) break;
+            const int kb = split ? 0 : kg * KPW + j;
+            if (kb * 32 + l32 >= item.key_len) continue;
+            if (item.partial < 0) {
+                const size_t row = (size_t)bh * N + item.key_start + kb * 32 + l32;
+                T *dkp = static_cast<T *>(a.dk) + row * D + db * 32, *dvp = static_cast<T *>(a.dv) + row * D + db * 32;
 #pragma unroll
-                for (int b = 0; b < DB; ++b)
+                for (int g = 0; g < 4; ++g) {
+                    const int x = g * 8 + half * 4;
+                    Io<T>::store4(dkp + x, dk[j][4 * g] * dks, dk[j][4 * g + 1] * dks, dk[j][4 * g + 2] * dks,
+                                  dk[j][4 * g + 3] * dks);
+                    Io<T>::store4(dvp + x, dv[j][4 * g], dv[j][4 * g + 1], dv[j][4 * g + 2], dv[j][4 * g + 3]);
+                }
+            } else {
+                const size_t prow = ((size_t)bh * a.n_partials + item.partial) * kKeyTile + kb * 32 + l32;
+                float *dkp = a.tpart_k + prow * D + db * 32, *dvp = a.tpart_v + prow * D + db * 32;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) xch[((w4 * DB + b) * 16 + i) * 64 + lane] = acc[b][i];
-            }
-            __syncthreads();
-            if (wave == 4) {
-#pragma unroll
-                for (int b = 0; b < DB; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        float v = 0.f;
-#pragma unroll
-                        for (int w = 0; w < 4; ++w) v += xch[((w * DB + b) * 16 + i) * 64 + lane];
-                        acc[b][i] = v;
-                    }
+                for (int g = 0; g < 4; ++g) {
+                    const int x = g * 8 + half * 4;
+                    Io<float>::store4(dkp + x, dk[j][4 * g] * dks, dk[j][4 * g + 1] * dks, dk[j][4 * g + 2] * dks,
+                                      dk[j][4 * g + 3] * dks);
+                    Io<float>::store4(dvp + x, dv[j][4 * g], dv[j][4 * g + 1], dv[j][4 * g + 2], dv[j][4 * g + 3]);
+                }
             }
         }
-        if (wave != 4) return;
-    }
-    if (!grad_role || !wave_active || l32 >= nk) return;
-    const float dks = -a.scale;       // the accumulator holds -dK
-    if (item.partial < 0) {
-        T *dkp = static_cast<T *>(a.dk) + ((size_t)bh * N + key) * D;
-        T *dvp = static_cast<T *>(a.dv) + ((size_t)bh * N + key) * D;
-#pragma unroll
-        for (int b = 0; b < DB; ++b)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int x = b * 32 + g * 8 + half * 4;
-                Io<T>::store4(dkp + x, dkacc[b][4 * g] * dks, dkacc[b][4 * g + 1] * dks, dkacc[b][4 * g + 2] * dks,
-                              dkacc[b][4 * g + 3] * dks);
-                Io<T>::store4(dvp + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
-            }
-    } else {
-        const size_t prow = ((size_t)bh * a.n_partials + item.partial) * kKeyTile + kblk * 32 + l32;
-        float *dkp = a.tpart_k + prow * D, *dvp = a.tpart_v + prow * D;
-#pragma unroll
-        for (int b = 0; b < DB; ++b)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int x = b * 32 + g * 8 + half * 4;
-                Io<float>::store4(dkp + x, dkacc[b][4 * g] * dks, dkacc[b][4 * g + 1] * dks, dkacc[b][4 * g + 2] * dks,
-                                  dkacc[b][4 * g + 3] * dks);
-                Io<float>::store4(dvp + x, dvacc[b][4 * g], dvacc[b][4 * g + 1], dvacc[b][4 * g + 2], dvacc[b][4 * g + 3]);
-            }
     }
 }
 

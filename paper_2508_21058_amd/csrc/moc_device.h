@@ -246,31 +246,31 @@ __device__ __forceinline__ uint32_t lds_address(const void *p) {
 }
 __device__ __forceinline__ void async_copy16(const void *g, void *lds) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(g), "s"(lds_address(lds)) : "memory", "m0");
+                 :: "v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_address(lds))) : "memory", "m0");
 }
 // wave-uniform base pointer + 32-bit unsigned byte offset per lane
 __device__ __forceinline__ void async_copy16(const void *base, uint32_t off, void *lds) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(off), "s"(base), "s"(lds_address(lds)) : "memory", "m0");
+                 :: "v"(off), "s"(uniform_ptr(base)), "s"(__builtin_amdgcn_readfirstlane(lds_address(lds))) : "memory", "m0");
 }
 // the same with the LDS destination given as an address (see lds_address)
 __device__ __forceinline__ void async_copy16_at(const void *g, uint32_t lds) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(g), "s"(lds) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(g), "s"(__builtin_amdgcn_readfirstlane(lds)) : "memory", "m0");
 }
 __device__ __forceinline__ void async_copy16_at(const void *base, uint32_t off, uint32_t lds) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(off), "s"(uniform_ptr(base)), "s"(lds) : "memory", "m0");
+                 :: "v"(off), "s"(uniform_ptr(base)), "s"(__builtin_amdgcn_readfirstlane(lds)) : "memory", "m0");
 }
 __device__ __forceinline__ void async_copy4_at(const void *g, uint32_t lds) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" :: "v"(g), "s"(lds) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" :: "v"(g), "s"(__builtin_amdgcn_readfirstlane(lds)) : "memory", "m0");
 }
 __device__ __forceinline__ void async_copy4_at(const void *base, uint32_t off, uint32_t lds) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-                 :: "v"(off), "s"(uniform_ptr(base)), "s"(lds) : "memory", "m0");
+                 :: "v"(off), "s"(uniform_ptr(base)), "s"(__builtin_amdgcn_readfirstlane(lds)) : "memory", "m0");
 }
 __device__ __forceinline__ void async_copy4(const void *g, void *lds) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-                 :: "v"(g), "s"(lds_address(lds)) : "memory", "m0");
+                 :: "v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_address(lds))) : "memory", "m0");
 }
 
 // max (or sum) of a value with its counterpart in the other half-wave, in all
