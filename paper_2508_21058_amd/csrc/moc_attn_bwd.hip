@@ -558,10 +558,14 @@ template <int D, int QOFF, int DOOFF>
 __device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &lo_n, const float *stats_n,
                                            const float *stats_c, const bf16x8 *kf, const bf16x8 *nvf, f32x16 &s_nxt,
                                            f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, char *pds, float c, int lane) {
-    constexpr int KS = D / 16, EPS = 16 / KS;      // vector elements handled per contraction step
+    constexpr int KS = D / 16;
+    constexpr int PRE = 4;                         // vector elements done while the tile reads are in flight
+    constexpr int EPS = (16 - PRE + KS - 1) / KS;  // ... per contraction step after that
     const int half = lane >> 5;
     bf16x8 qa[KS], da[KS];
     f32x4 l4[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) l4[g] = *reinterpret_cast<const f32x4 *>(stats_c + g * 16 + half * 4);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         qa[s] = lo_n.template frag<QOFF>(smem, s);
@@ -572,19 +576,22 @@ __device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &
         const f32x4 d4 = *reinterpret_cast<const f32x4 *>(stats_n + g * 16 + 8 + half * 4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) dp_nxt[4 * g + e] = d4[e];
-        l4[g] = *reinterpret_cast<const f32x4 *>(stats_c + g * 16 + half * 4);
     }
+    auto vec = [&](int i) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(s_cur[i], c, -l4[i >> 2][i & 3]));
+        s_cur[i] = p;
+        dp_cur[i] *= p;
+    };
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < PRE; ++i) vec(i);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         s_nxt = mfma32(qa[s], kf[s], s == 0 ? zero16() : s_nxt);
         dp_nxt = mfma32(da[s], nvf[s], dp_nxt);
 #pragma unroll
-        for (int i = s * EPS; i < (s + 1) * EPS; ++i) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(s_cur[i], c, -l4[i >> 2][i & 3]));
-            s_cur[i] = p;
-            dp_cur[i] *= p;
-        }
+        for (int i = PRE + s * EPS; i < PRE + (s + 1) * EPS && i < 16; ++i) vec(i);
         __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
