@@ -272,6 +272,7 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
     m->n_text_tiles = int32_t(ttiles.size());
     m->n_partials = n_partials;
     m->h_off.assign(off, off + C + 1);
+    for (int j = 0; j < C; ++j) m->max_chunk_len = std::max(m->max_chunk_len, off[j + 1] - off[j]);
     m->h_kind = kind;
     m->h_win = win;
 

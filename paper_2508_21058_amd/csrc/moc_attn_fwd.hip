@@ -22,14 +22,33 @@ namespace moc {
 // tile at VOFF. Rows >= valid of a ragged tile hold copies of the last valid key
 // and are masked to -inf. LDS reads are pinned a few fragments ahead of the
 // matrix instructions that consume them.
-template <int D, int KOFF, int VOFF>
+// LEAN stages the K fragments of one 32-key block at a time (half the registers).
+template <int D, int KOFF, int VOFF, bool LEAN = false>
 __device__ __forceinline__ void fwd_tile(const char *smem, LaneOffs<D> &lo, const bf16x8 *qf, f32x16 *oacc,
                                          float &m_run, float &l_run, float c, int valid, int lane) {
     constexpr int KS = D / 16, DB = D / 32;
     const int half = lane >> 5;
     lo.pin();
     f32x16 sacc[2];
-    {
+    if (LEAN) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            bf16x8 kf[KS];
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                kf[s] = kb == 0 ? lo.template frag<KOFF>(smem, s) : lo.template frag<KOFF + 32 * D * 2>(smem, s);
+            sacc[kb] = mfma32(kf[0], qf[0], zero16());
+#pragma unroll
+            for (int s = 1; s < KS; ++s) sacc[kb] = mfma32(kf[s], qf[s], sacc[kb]);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+            for (int u = 0; u < KS - 4; ++u) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        }
+    } else {
         bf16x8 kf[2 * KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) kf[s] = lo.template frag<KOFF>(smem, s);
@@ -190,6 +209,140 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
     if (row_valid && half == 0) a.plse[prow] = m_run * a.scale + __logf(l_tot);
 }
 
+// Routed items, chunk-stationary (bf16 storage, chunks of at most kChunkRows
+// keys): the K and V rows of a chunk stay in LDS while the chunk's inverse list
+// streams past. A workgroup takes kGroupTiles consecutive routed items (128
+// list entries each, usually of one or two chunks); per chunk it loads K / V
+// once, then its eight waves work through the 32-query blocks on their own:
+// query fragments straight from global memory into registers, the
+// online-softmax recurrence over the resident key tiles, the normalised partial
+// output and its log-sum-exp into the slot of the (query, link) pair. Inside a
+// chunk there is no barrier and no shared staging, so one wave's memory and
+// LDS latencies are covered by the other wave of its SIMD.
+constexpr int kChunkRows = 288;       // resident keys (K region; the V region holds 32 rows more, see below)
+constexpr int kGroupTiles = 16;
+
+template <int D>
+__global__ __launch_bounds__(512, 1) void attn_fwd_chunk_kernel(FwdArgs a) {
+    typedef bf16_t T;
+    constexpr int KS = D / 16, DB = D / 32;
+    constexpr int RB = D * 2;                     // bytes per row
+    constexpr int KBYTES = kChunkRows * RB;       // K region; the last 64-key tile may run 32 rows into the V region
+    constexpr int VBYTES = (kChunkRows + 32) * RB;   // (those keys are masked), so the V region is a full tile longer
+    constexpr int RPI = 1024 / RB;                // rows per copy instruction
+    __shared__ __attribute__((aligned(1024))) char smem[KBYTES + VBYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    const int N = a.N, C = a.C;
+    const int groups_per_head = (a.items_per_head + kGroupTiles - 1) / kGroupTiles;
+    int logical;
+    if (!xcd_remap((long long)groups_per_head * a.BH, logical)) return;
+    const int bh = logical / groups_per_head;
+    const int32_t *toff = a.tile_off + (size_t)bh * (C + 1);
+    const int32_t *loff = a.list_off + (size_t)bh * (C + 1);
+    int t0 = (logical - bh * groups_per_head) * kGroupTiles;
+    const int t1 = min(t0 + kGroupTiles, toff[C]);
+    if (t0 >= t1) return;
+    int j;
+    {
+        int lo = 0, hi = C;   // largest j with toff[j] <= t0
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (toff[mid] <= t0) lo = mid; else hi = mid;
+        }
+        j = lo;
+    }
+    const char *qbase = static_cast<const char *>(a.q) + (size_t)bh * N * RB;
+    const char *kbase = static_cast<const char *>(a.k) + (size_t)bh * N * RB;
+    const char *vbase = static_cast<const char *>(a.v) + (size_t)bh * N * RB;
+    const float c = a.scale_log2;
+    LaneOffs<D> lo;
+    lo.init(lane);
+    const int rlo = lane / (D / 8), cgp = lane % (D / 8);
+
+    while (t0 < t1) {
+        while (toff[j + 1] <= t0) ++j;            // chunk of tile t0 (chunks without routed queries have no tiles)
+        const int te = min(t1, toff[j + 1]);      // this chunk's tiles in the group: [t0, te)
+        const int key0 = a.off[j], len = a.off[j + 1] - key0;
+        const int ntile = (len + 63) >> 6;
+        // ---- K / V of the chunk -> LDS (rows past the end repeat the last row: finite, and masked as keys)
+        {
+            const int nk = (min(ntile * 64, kChunkRows) + RPI - 1) / RPI, nv = ntile * 64 / RPI;
+            for (int i = wave; i < nk + nv; i += 8) {
+                const bool isk = i < nk;
+                const int ii = isk ? i : i - nk;
+                const int row = ii * RPI + rlo;
+                const uint32_t off = (uint32_t)(min(row, len - 1) * RB + ((cgp ^ SwTile<D>::sw(row)) << 4));
+                async_copy16((isk ? kbase : vbase) + (size_t)key0 * RB, off, smem + (isk ? 0 : KBYTES) + ii * 1024);
+            }
+            wait_vmcnt<0>();
+            __syncthreads();
+        }
+        // ---- the chunk's list entries covered by tiles [t0, te)
+        const int cnt = loff[j + 1] - loff[j];
+        const int q_first = (t0 - toff[j]) * kBM;
+        const int nq = min(cnt, (te - toff[j]) * kBM) - q_first;
+        const int32_t *entries = a.qlist + (size_t)bh * N * a.topk + loff[j] + q_first;
+        // software pipeline over the wave's blocks: the list entry of the next block is loaded
+        // before the first key tile of the current one, its query fragments after it
+        auto entry_of = [&](int blk) { return entries[min(blk * 32 + l32, nq - 1)]; };
+        auto load_q = [&](int e, bf16x8 *qf) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                qf[s] = Io<T>::load8(reinterpret_cast<const T *>(qbase + (size_t)(e >> 5) * RB) + s * 16 + half * 8);
+        };
+        int blk = wave;
+        int e_cur = 0;
+        bf16x8 qf[KS];
+        if (blk * 32 < nq) { e_cur = entry_of(blk); load_q(e_cur, qf); }
+        while (blk * 32 < nq) {
+            const bool more = (blk + 8) * 32 < nq;
+            int e_nxt = e_cur;
+            if (more) e_nxt = entry_of(blk + 8);
+            f32x16 oacc[DB];
+#pragma unroll
+            for (int b = 0; b < DB; ++b) oacc[b] = zero16();
+            float m_run = -INFINITY, l_run = 0.f;
+            fwd_tile<D, 0, KBYTES, true>(smem, lo, qf, oacc, m_run, l_run, c, min(64, len), lane);
+            bf16x8 qn[KS];
+            if (more) load_q(e_nxt, qn);
+            for (int t = 1; t < ntile; ++t)
+                fwd_tile<D, 0, KBYTES, true>(smem + t * 64 * RB, lo, qf, oacc, m_run, l_run, c, min(64, len - t * 64), lane);
+            const float l_tot = xhalf_sum(l_run);
+            const float inv = 1.f / l_tot;
+            const size_t prow = ((size_t)bh * N + (e_cur >> 5)) * a.slots + (e_cur & 31);
+            // The two half-waves hold adjacent 4-feature pieces of the same query: exchange them so
+            // that the lower half stores features [16 u, 16 u + 8) and the upper half [16 u + 8, 16 u + 16)
+            // of a 32-feature block as one 16-byte word each.
+            if (blk * 32 + l32 < nq) {
+                T *dst = a.po + prow * D + half * 8;
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const int g = 2 * u;
+                        const uint32_t x0 = pack_bf16(oacc[b][4 * g] * inv, oacc[b][4 * g + 1] * inv);
+                        const uint32_t x1 = pack_bf16(oacc[b][4 * g + 2] * inv, oacc[b][4 * g + 3] * inv);
+                        const uint32_t y0 = pack_bf16(oacc[b][4 * g + 4] * inv, oacc[b][4 * g + 5] * inv);
+                        const uint32_t y1 = pack_bf16(oacc[b][4 * g + 6] * inv, oacc[b][4 * g + 7] * inv);
+                        const auto r0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+                        const auto r1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+                        const u32x4 w = {r0[0], r1[0], r0[1], r1[1]};
+                        *reinterpret_cast<u32x4 *>(dst + b * 32 + u * 16) = w;
+                    }
+                if (half == 0) a.plse[prow] = m_run * a.scale + __logf(l_tot);
+            }
+            blk += 8;
+            e_cur = e_nxt;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) qf[s] = qn[s];
+        }
+        t0 = te;
+        if (t0 < t1) __syncthreads();             // every wave is done with this chunk's K / V
+    }
+}
+
 // o = sum_s exp(lse_s - lse) o_s over the forced-link slot and the used routed slots
 template <int D, typename T>
 __global__ __launch_bounds__(256) void fwd_merge_kernel(const bf16_t *__restrict__ po,
@@ -249,7 +402,16 @@ static hipError_t fwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, const int3
     if (a.topk > 0) {
         a.items_per_head = (m->N * a.topk + kBM - 1) / kBM + m->C;   // upper bound; surplus items exit at once
         MOC_PROF("attn_fwd_routed", st);
-        attn_fwd_kernel<D, T, MODE_ROUTED><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a);
+        if constexpr (sizeof(T) == 2) {
+            if (m->max_chunk_len <= kChunkRows) {
+                const int groups = (a.items_per_head + kGroupTiles - 1) / kGroupTiles;
+                attn_fwd_chunk_kernel<D><<<dim3(xcd_grid((long long)groups * BH)), dim3(512), 0, st>>>(a);
+            } else {
+                attn_fwd_kernel<D, T, MODE_ROUTED><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a);
+            }
+        } else {
+            attn_fwd_kernel<D, T, MODE_ROUTED><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a);
+        }
     }
     { MOC_PROF("attn_fwd_forced", st);
     a.items_per_head = m->n_atiles;

@@ -36,6 +36,7 @@ struct TextTile { int32_t key_start, key_len, first_partial, n_partials; };
 struct moc_meta {
     int32_t N = 0, C = 0, T = 0, W = 0;
     int32_t n_atiles = 0, n_ranges = 0, n_kvitems = 0, n_text_tiles = 0, n_partials = 0;
+    int32_t max_chunk_len = 0;
     void *d_base = nullptr;
     size_t d_bytes = 0;
     int32_t *d_off = nullptr;        // [C+1]
