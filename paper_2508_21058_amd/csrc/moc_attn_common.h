@@ -26,6 +26,10 @@ struct FwdArgs {
     // backward only
     const void *d_o;
     const float *lse, *delta;
+    // forced-link forward items with the merge fused into their epilogue
+    const int32_t *sel;     // [BH, N, topk] selections (which routed slots are in use)
+    void *o_out;            // [BH, N, D] final output
+    float *lse_out;         // [BH, N] final log-sum-exp
 };
 
 // The GPU has 8 XCDs with private L2 caches and hands consecutive workgroups to

@@ -124,6 +124,95 @@ __device__ __forceinline__ void fwd_tile(const char *smem, LaneOffs<D> &lo, cons
     __builtin_amdgcn_sched_group_barrier(0x008, 2 * DB, 0);
 }
 
+// Epilogue of the forced-link items when the routed items of the same pass have
+// already run: instead of storing its partial and leaving the combination to a
+// merge kernel, the wave combines right here (the split-softmax identity
+// o = sum_s exp(lse_s - lse) o_s over the forced-link slot and the used routed
+// slots). One lane per query turns the <= topk+1 partial log-sum-exps into
+// weights; the forced-link part, already weighted, is transposed through the
+// wave's LDS patch as in store_rows_bf16; then every lane owns 8 features of a
+// row, adds the weighted routed partials (16-byte loads, a batch in flight) and
+// stores the final row. The forced-link partial never goes to memory.
+// `smem` must be free (barrier before); needs 4 * (32 * (D + 4) + 64) * 2 + 4 * 32 * 34 * 4 bytes.
+template <int D>
+__device__ __forceinline__ void merge_store_rows(char *smem, int wave, int lane, const f32x16 *acc, float m_run,
+                                                 float l_tot, bool row_valid, int qi, size_t bhN, const FwdArgs &a) {
+    constexpr int DB = D / 32, RS = D + 4, WS = 34;    // WS: floats per row of the weight table (32 weights, lse)
+    const int half = lane >> 5, l32 = lane & 31;
+    const int topk = a.topk, slots = topk + 1;
+    bf16_t *patch = reinterpret_cast<bf16_t *>(smem) + wave * (32 * RS + 64);
+    int32_t *rowidx = reinterpret_cast<int32_t *>(patch + 32 * RS);
+    float *wts = reinterpret_cast<float *>(smem + 4 * (32 * RS + 64) * 2) + wave * 32 * WS;
+    float wf = 0.f;
+    if (half == 0) {
+        const size_t row = bhN + qi;
+        const float lf = m_run * a.scale + __logf(l_tot);
+        const float *pl = a.plse + row * slots;
+        const int32_t *sr = a.sel + row * topk;
+        float mx = lf;
+        for (int s = 0; s < topk; ++s) {
+            const int j = sr[s];
+            if (j >= 0 && j < a.C) mx = fmaxf(mx, pl[s]);
+        }
+        float z = __expf(lf - mx);
+        for (int s = 0; s < topk; ++s) {
+            const int j = sr[s];
+            if (j >= 0 && j < a.C) z += __expf(pl[s] - mx);
+        }
+        const float tot = mx + __logf(z);
+        for (int s = 0; s < topk; ++s) {
+            const int j = sr[s];
+            wts[l32 * WS + s] = (j >= 0 && j < a.C) ? __expf(pl[s] - tot) : 0.f;
+        }
+        wts[l32 * WS + 32] = tot;
+        wf = __expf(lf - tot);
+        rowidx[l32] = row_valid ? qi : -1;
+    }
+    wf = xhalf_sum(wf);                                // the other half-wave holds the same query
+    const float scale = wf / l_tot;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            Io<bf16_t>::store4(patch + l32 * RS + b * 32 + g * 8 + half * 4, acc[b][4 * g] * scale,
+                               acc[b][4 * g + 1] * scale, acc[b][4 * g + 2] * scale, acc[b][4 * g + 3] * scale);
+    __builtin_amdgcn_wave_barrier();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    constexpr int LPR = D / 8, RPI = 64 / LPR;          // lanes per row, rows per instruction
+    const int cg = lane % LPR, r0 = lane / LPR;
+    const bf16_t *qsafe = static_cast<const bf16_t *>(a.q);      // finite values for the loads of unused slots
+    for (int it = 0; it < 32 / RPI; ++it) {
+        const int r = it * RPI + r0;
+        const int dr = rowidx[r];
+        if (dr < 0) continue;
+        const size_t row = bhN + dr;
+        float o8[8];
+        {
+            const u32x2 lo2 = *reinterpret_cast<const u32x2 *>(patch + r * RS + cg * 8);
+            const u32x2 hi2 = *reinterpret_cast<const u32x2 *>(patch + r * RS + cg * 8 + 4);
+            o8[0] = bf16_lo(lo2[0]); o8[1] = bf16_hi(lo2[0]); o8[2] = bf16_lo(lo2[1]); o8[3] = bf16_hi(lo2[1]);
+            o8[4] = bf16_lo(hi2[0]); o8[5] = bf16_hi(hi2[0]); o8[6] = bf16_lo(hi2[1]); o8[7] = bf16_hi(hi2[1]);
+        }
+        const bf16_t *pbase = a.po + row * slots * D + cg * 8;
+        for (int s0 = 0; s0 < topk; s0 += 8) {
+            float w[8], f[8][8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int s = s0 + u;
+                w[u] = s < topk ? wts[r * WS + s] : 0.f;
+                const bf16_t *src = w[u] != 0.f ? pbase + (size_t)s * D : qsafe + row * D + cg * 8;
+                Io<bf16_t>::load8f(src, f[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o8[e] = fmaf(w[u], f[u][e], o8[e]);
+        }
+        Io<bf16_t>::store8(static_cast<bf16_t *>(a.o_out) + row * D + cg * 8, o8);
+        if (cg == 0) a.lse_out[row] = wts[r * WS + 32];
+    }
+}
+
 template <int D, typename T, int MODE>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
     constexpr int BN = 64;
@@ -204,6 +293,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
     __syncthreads();      // every wave is done with the tile buffers: reuse them for the output transpose
     const float l_tot = xhalf_sum(l_run);
     const float inv = 1.f / l_tot;
+    if constexpr (MODE == MODE_ANCHOR && sizeof(T) == 2) {
+        if (a.o_out) {      // the routed items are done: combine here, no forced-link partial, no merge kernel
+            merge_store_rows<D>(smem, wave, lane, oacc, m_run, l_tot, row_valid, qi, (size_t)bh * N, a);
+            return;
+        }
+    }
     const size_t prow = ((size_t)bh * N + qi) * a.slots + slot;
     store_rows_bf16<D>(smem, wave, lane, oacc, inv, row_valid ? (int)prow : -1, a.po);
     if (row_valid && half == 0) a.plse[prow] = m_run * a.scale + __logf(l_tot);
@@ -413,9 +508,14 @@ static hipError_t fwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, const int3
             attn_fwd_kernel<D, T, MODE_ROUTED><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a);
         }
     }
+    // bf16 storage: the forced-link items run after the routed ones and merge in their epilogue
+    // (needs the LDS of the tile buffers to hold the transposition patches and the weight table)
+    const bool fuse = sizeof(T) == 2 && 4 * (32 * (D + 4) + 64) * 2 + 4 * 32 * 34 * 4 <= 4 * 64 * D * 2;
     { MOC_PROF("attn_fwd_forced", st);
     a.items_per_head = m->n_atiles;
+    a.sel = sel; a.o_out = fuse ? o : nullptr; a.lse_out = lse;
     attn_fwd_kernel<D, T, MODE_ANCHOR><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a); }
+    if (fuse) return hipGetLastError();
     MOC_PROF("fwd_merge", st);
     constexpr int QPW = 256 / (D / 8);
     fwd_merge_kernel<D, T><<<dim3((m->N + QPW - 1) / QPW, BH), dim3(256), 0, st>>>(
