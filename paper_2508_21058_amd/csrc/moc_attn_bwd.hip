@@ -106,6 +106,76 @@ __device__ __forceinline__ void dq_half_tile(const char *smem, LaneOffs<D> &lo, 
     }
 }
 
+// Epilogue of the forced-link dQ items when the routed items of the same pass
+// have already run: dQ of a query is the sum of its forced-link part and of the
+// partials in its used routed slots, so the wave adds them right here instead
+// of storing its own partial for a merge kernel. The forced-link part is
+// transposed through the wave's LDS patch (as in store_rows_bf16); then every
+// lane owns 8 features of a row, adds the routed partials (16-byte loads, a
+// batch in flight) and stores the final row.
+// `smem` must be free (barrier before); needs 4 * (32 * (D + 4) + 128) * 2 bytes.
+template <int D>
+__device__ __forceinline__ void sum_store_rows(char *smem, int wave, int lane, const f32x16 *acc, float scale,
+                                               bool row_valid, int qi, size_t bhN, const FwdArgs &a) {
+    constexpr int DB = D / 32, RS = D + 4;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int topk = a.topk, slots = topk + 1;
+    bf16_t *patch = reinterpret_cast<bf16_t *>(smem) + wave * (32 * RS + 128);
+    int32_t *rowidx = reinterpret_cast<int32_t *>(patch + 32 * RS);
+    uint32_t *used = reinterpret_cast<uint32_t *>(rowidx + 32);
+    if (half == 0) {
+        const int32_t *sr = a.sel + (bhN + qi) * topk;
+        uint32_t mask = 0;
+        for (int s = 0; s < topk; ++s) {
+            const int j = sr[s];
+            if (j >= 0 && j < a.C) mask |= 1u << s;
+        }
+        used[l32] = mask;
+        rowidx[l32] = row_valid ? qi : -1;
+    }
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            Io<bf16_t>::store4(patch + l32 * RS + b * 32 + g * 8 + half * 4, acc[b][4 * g] * scale,
+                               acc[b][4 * g + 1] * scale, acc[b][4 * g + 2] * scale, acc[b][4 * g + 3] * scale);
+    __builtin_amdgcn_wave_barrier();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    constexpr int LPR = D / 8, RPI = 64 / LPR;          // lanes per row, rows per instruction
+    const int cg = lane % LPR, r0 = lane / LPR;
+    const bf16_t *qsafe = static_cast<const bf16_t *>(a.q);      // finite values for the loads of unused slots
+    for (int it = 0; it < 32 / RPI; ++it) {
+        const int r = it * RPI + r0;
+        const int dr = rowidx[r];
+        if (dr < 0) continue;
+        const size_t row = bhN + dr;
+        const uint32_t mask = used[r];
+        float o8[8];
+        {
+            const u32x2 lo2 = *reinterpret_cast<const u32x2 *>(patch + r * RS + cg * 8);
+            const u32x2 hi2 = *reinterpret_cast<const u32x2 *>(patch + r * RS + cg * 8 + 4);
+            o8[0] = bf16_lo(lo2[0]); o8[1] = bf16_hi(lo2[0]); o8[2] = bf16_lo(lo2[1]); o8[3] = bf16_hi(lo2[1]);
+            o8[4] = bf16_lo(hi2[0]); o8[5] = bf16_hi(hi2[0]); o8[6] = bf16_lo(hi2[1]); o8[7] = bf16_hi(hi2[1]);
+        }
+        const bf16_t *pbase = a.po + row * slots * D + cg * 8;
+        for (int s0 = 0; s0 < topk; s0 += 8) {
+            float w[8], f[8][8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int s = s0 + u;
+                const bool ok = s < topk && ((mask >> s) & 1u);
+                w[u] = ok ? 1.f : 0.f;
+                Io<bf16_t>::load8f(ok ? pbase + (size_t)s * D : qsafe + row * D + cg * 8, f[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o8[e] = fmaf(w[u], f[u][e], o8[e]);
+        }
+        Io<bf16_t>::store8(static_cast<bf16_t *>(a.o_out) + row * D + cg * 8, o8);
+    }
+}
+
 template <int D, typename T, int MODE>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(FwdArgs a) {
     constexpr int BN = 64;
@@ -186,6 +256,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(FwdArgs a) {
     }
 
     __syncthreads();      // tile buffers are free: reuse them for the output transpose
+    if constexpr (MODE == MODE_ANCHOR && sizeof(T) == 2) {
+        if (a.o_out) {      // the routed items are done: sum here, no forced-link partial, no merge kernel
+            sum_store_rows<D>(smem, wave, lane, dqacc, a.scale, row_valid, qi, (size_t)bh * N, a);
+            return;
+        }
+    }
     const size_t prow = ((size_t)bh * N + qi) * a.slots + slot;
     store_rows_bf16<D>(smem, wave, lane, dqacc, a.scale, row_valid ? (int)prow : -1, a.po);
 }
@@ -1046,7 +1122,10 @@ static hipError_t bwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, KvArgs &kv
     }
     { MOC_PROF("attn_bwd_dq_forced", st);
     a.items_per_head = m->n_atiles;
+    // bf16 storage: the forced-link items run after the routed ones and add the routed partials themselves
+    a.sel = sel; a.o_out = sizeof(T) == 2 ? dq : nullptr;
     attn_bwd_dq_kernel<D, T, MODE_ANCHOR><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a); }
+    if (sizeof(T) == 2) return hipGetLastError();
     MOC_PROF("dq_merge", st);
     dq_merge_kernel<D, T><<<dim3((m->N + QPW - 1) / QPW, BH), dim3(256), 0, st>>>(a.po, sel, m->N, m->C, a.topk,
                                                                                 static_cast<T *>(dq));
