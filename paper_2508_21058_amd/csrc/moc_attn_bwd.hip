@@ -690,9 +690,10 @@ __device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &
 // tile t+1 sit between the vector instructions of tile t, and the copy
 // addressing is kept to a few scalar and vector operations per tile.
 //
-// Step t (t = -1 .. ntiles), one workgroup barrier per step:
+// Step t (t = -1 .. ntiles+1), one workgroup barrier per step:
 //   score waves: matrix half on tile t+1, vector half on tile t -> P/dS buffer t&1
-//   grad waves : tile t-1 with P/dS buffer (t-1)&1
+//   grad waves : read Q^T / dO^T of tile t-1 and P/dS buffer (t-1)&1 into registers, multiply what
+//                they read the step before (tile t-2)
 // so tiles t-1 .. t+1 are resident and the stage of tile t-2 is free.
 // The query stream of an item is mostly a gather of rows scattered over the
 // sequence, so one tile of look-ahead does not cover the memory latency: the
@@ -816,9 +817,10 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
             }
             wait_lgkm0();
             step_barrier();                                           // step ntiles
+            step_barrier();                                           // step ntiles + 1 (the gradient waves' last)
         } else {
             int st = NS - 1;     // stage of tile t
-            for (int t = -1; t <= ntiles; ++t) {
+            for (int t = -1; t <= ntiles + 1; ++t) {
                 step_barrier();
                 if (t >= 0 && t < ntiles && mine(t)) {
                     f32x16 sacc, dpacc;
@@ -989,49 +991,71 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
             return f;
         };
         const char *const pds_rd = pds_s + lane * 16;
-        // tile u with fragments f: P / dS of key block slot kb0 + j feed accumulator j
-        auto gmfma = [&](const TFrags &f, int u, int j) {
+        // P / dS fragments of tile u, key block slot kb0 + j: P step 0, P step 1, dS step 0, dS step 1
+        auto pload = [&](int u, int j, bf16x8 *P) {
             const int kb0 = split ? (u & 3) : kg * KPW;
             const char *pp = pds_rd + ((u & 1) << 14) + (kb0 + j) * 4096;
-            const bf16x8 pf0 = *reinterpret_cast<const bf16x8 *>(pp);
-            const bf16x8 pf1 = *reinterpret_cast<const bf16x8 *>(pp + 1024);
-            const bf16x8 dsf0 = *reinterpret_cast<const bf16x8 *>(pp + 2048);
-            const bf16x8 dsf1 = *reinterpret_cast<const bf16x8 *>(pp + 3072);
-            dv[j] = mfma32(f.dot[0], pf0, dv[j]);
-            dk[j] = mfma32(f.qt[0], dsf0, dk[j]);
-            dv[j] = mfma32(f.dot[1], pf1, dv[j]);
-            dk[j] = mfma32(f.qt[1], dsf1, dk[j]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) P[i] = *reinterpret_cast<const bf16x8 *>(pp + i * 1024);
         };
-        // The transposed fragments of a tile are read one step early, while the workgroup is
-        // still on its way to the barrier that publishes the tile's P / dS; the copies of a
-        // step go out in the middle of its matrix work.
+        auto gmfma = [&](const TFrags &f, const bf16x8 *P, int j) {
+            dv[j] = mfma32(f.dot[0], P[0], dv[j]);
+            dk[j] = mfma32(f.qt[0], P[2], dk[j]);
+            dv[j] = mfma32(f.dot[1], P[1], dv[j]);
+            dk[j] = mfma32(f.qt[1], P[3], dk[j]);
+        };
         step_wait(-1);
         step_issue(-1);
         step_wait(0);
         step_issue(0);
-        TFrags f = tload(0);
-        int st = 0;      // stage of tile t - 1
         if (nmine == KPW) {
-            for (int t = 1; t <= ntiles; ++t) {
+            // Two steps behind the score waves: everything a step multiplies was read into registers
+            // during the step before (the P / dS of tile t-2 were published by the barrier of step
+            // t-1), so the matrix instructions start right after the barrier, and the reads for the
+            // next step are issued behind them, key block by key block, into the registers they free.
+            // The reads must be over before the next barrier: the score waves then rewrite that buffer.
+            step_wait(1);
+            step_issue(1);
+            bf16x8 P[KPW][4];
+#pragma unroll
+            for (int j = 0; j < KPW; ++j) pload(0, j, P[j]);
+            TFrags f = tload(0);
+            int st = 0;      // stage of the tile held in f (tile t - 2 at the top of step t)
+            wait_lgkm0();
+            for (int t = 2; t <= ntiles + 1; ++t) {
                 step_wait(t);
+                const int stn = t - 1 < ntiles ? next_stage(st) : st;     // past the end: any resident tile, unused
 #pragma unroll
-                for (int j = 0; j < KPW / 2; ++j) gmfma(f, t - 1, j);
-                step_issue(t);
-#pragma unroll
-                for (int j = KPW / 2; j < KPW; ++j) gmfma(f, t - 1, j);
-                // next tile (the last step reads the same tile again: the values are not used)
-                st = t < ntiles ? next_stage(st) : st;
-                f = tload(st);
+                for (int j = 0; j < KPW; ++j) {
+                    gmfma(f, P[j], j);
+                    __builtin_amdgcn_sched_barrier(0);
+                    pload(t - 1, j, P[j]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (j == KPW / 2 - 1) step_issue(t);
+                }
+                f = tload(stn);
+                st = stn;
+                wait_lgkm0();
             }
         } else {
-            for (int t = 1; t <= ntiles; ++t) {
+            // one step behind, reading as it goes (partly filled or tail tiles)
+            TFrags f = tload(0);
+            int st = 0;      // stage of tile t - 1
+            for (int t = 1; t <= ntiles + 1; ++t) {
                 step_wait(t);
                 step_issue(t);
+                if (t <= ntiles) {
 #pragma unroll
-                for (int j = 0; j < KPW; ++j)
-                    if (j < nmine) gmfma(f, t - 1, j);
-                st = t < ntiles ? next_stage(st) : st;
-                f = tload(st);
+                    for (int j = 0; j < KPW; ++j)
+                        if (j < nmine) {
+                            bf16x8 P[4];
+                            pload(t - 1, j, P);
+                            gmfma(f, P, j);
+                        }
+                    st = t < ntiles ? next_stage(st) : st;
+                    f = tload(st);
+                    wait_lgkm0();
+                }
             }
         }
 
