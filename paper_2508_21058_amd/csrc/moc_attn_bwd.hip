@@ -635,8 +635,9 @@ __device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &
                                            const float *stats_c, const bf16x8 *kf, const bf16x8 *nvf, f32x16 &s_nxt,
                                            f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, char *pds, float c, int lane) {
     constexpr int KS = D / 16;
-    constexpr int PRE = 4;                         // vector elements done while the tile reads are in flight
-    constexpr int EPS = (16 - PRE + KS - 1) / KS;  // ... per contraction step after that
+    constexpr int PRE = 8;                         // vector elements done while the tile reads are in flight
+    constexpr int EPS = (16 - PRE) / KS;           // ... per contraction step after that
+    static_assert(PRE + EPS * KS == 16, "vector elements must divide evenly over the contraction steps");
     const int half = lane >> 5;
     bf16x8 qa[KS], da[KS];
     f32x4 l4[4];
@@ -658,6 +659,10 @@ __device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &
         s_cur[i] = p;
         dp_cur[i] *= p;
     };
+    auto emit = [&](int ks) {      // fragments of 16 queries, complete once elements [8 ks, 8 ks + 8) are done
+        *reinterpret_cast<bf16x8 *>(pds + ks * 1024) = acc_to_frag(s_cur, ks);
+        *reinterpret_cast<bf16x8 *>(pds + (2 + ks) * 1024) = acc_to_frag(dp_cur, ks);
+    };
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < PRE; ++i) vec(i);
@@ -666,15 +671,12 @@ __device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &
     for (int s = 0; s < KS; ++s) {
         s_nxt = mfma32(qa[s], kf[s], s == 0 ? zero16() : s_nxt);
         dp_nxt = mfma32(da[s], nvf[s], dp_nxt);
+        if (s == 0) emit(0);
 #pragma unroll
-        for (int i = PRE + s * EPS; i < PRE + (s + 1) * EPS && i < 16; ++i) vec(i);
+        for (int i = PRE + s * EPS; i < PRE + (s + 1) * EPS; ++i) vec(i);
         __builtin_amdgcn_sched_barrier(0);
     }
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        *reinterpret_cast<bf16x8 *>(pds + ks * 1024) = acc_to_frag(s_cur, ks);
-        *reinterpret_cast<bf16x8 *>(pds + (2 + ks) * 1024) = acc_to_frag(dp_cur, ks);
-    }
+    emit(1);
 }
 
 // bf16 storage. Eight waves per workgroup, two per SIMD, in two roles: waves
