@@ -928,9 +928,10 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
         // own copies of tile u landed: at most the copies of the younger tiles may be outstanding
         auto wait_tile = [&](int u) {
             const int younger = min(NS - 4, ntiles - 1 - u);
-            static_assert(NS - 4 == 3, "cases below");
-            if (younger >= 3) wait_vmcnt<3 * LPT>();
-            else if (younger == 2) wait_vmcnt<2 * LPT>();
+            static_assert(NS - 4 <= 4 && 4 * LPT < 64, "cases below");
+            if (younger >= 4) wait_vmcnt<(NS - 4 >= 4 ? 4 : 0) * LPT>();
+            else if (younger == 3) wait_vmcnt<(NS - 4 >= 3 ? 3 : 0) * LPT>();
+            else if (younger == 2) wait_vmcnt<(NS - 4 >= 2 ? 2 : 0) * LPT>();
             else if (younger == 1) wait_vmcnt<LPT>();
             else wait_vmcnt<0>();
         };
