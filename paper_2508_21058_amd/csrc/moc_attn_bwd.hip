@@ -81,12 +81,20 @@ __device__ __forceinline__ void dq_half_tile(const char *smem, LaneOffs<D> &lo, 
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     }
+    if (valid >= ROW0 + 32) {      // all 32 keys exist (wave-uniform): no masking in the common case
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int key = ROW0 + (i >> 2) * 8 + half * 4 + (i & 3);
-        float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, -lse2));
-        if (key >= valid) p = 0.f;
-        sacc[i] = p * (dpacc[i] - dl);
+        for (int i = 0; i < 16; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, -lse2));
+            sacc[i] = p * (dpacc[i] - dl);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int key = ROW0 + (i >> 2) * 8 + half * 4 + (i & 3);
+            float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, -lse2));
+            if (key >= valid) p = 0.f;
+            sacc[i] = p * (dpacc[i] - dl);
+        }
     }
     {
         bf16x8 ktf[DB];
