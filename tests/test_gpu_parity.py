@@ -163,6 +163,22 @@ def test_single_chunk_and_length_one_chunks():
     run_case(lay, 1, 1, 64, 4, torch.bfloat16, seed=37)
 
 
+def test_long_chunks_take_the_tiled_routed_path():
+    """Chunks of 520 keys do not fit the chunk-resident routed forward (<= 288 keys kept in LDS):
+    the query-tile x key-tile routed kernel must give the same answer (sweep config's chunk 520)."""
+    lay = mi.multishot_layout(1, 64, 2, 1040, 520, "frame")
+    run_case(lay, 1, 2, 128, 2, torch.bfloat16, seed=38)
+
+
+def test_chunk_of_288_keys_and_many_short_lists():
+    """The largest chunk the chunk-resident path takes (288 = 4.5 key tiles), next to chunks with
+    short inverse lists so one workgroup walks several chunks."""
+    lay = mi.multishot_layout(1, 24, 3, 576, 288, "chunk")
+    run_case(lay, 1, 2, 128, 3, torch.bfloat16, seed=39)
+    lay = mi.multishot_layout(2, 16, 4, 96, 24, "frame")       # 16 chunks per shot, ~100 list entries each
+    run_case(lay, 1, 2, 128, 4, torch.bfloat16, seed=40)
+
+
 def test_end_to_end_route_then_attend_matches_oracle_sets():
     """The library's own selection fed to its attention: rows whose set equals
     the oracle's must match the oracle's output."""
