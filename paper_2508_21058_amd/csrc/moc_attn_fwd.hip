@@ -83,8 +83,11 @@ __device__ __forceinline__ void fwd_tile(const char *smem, LaneOffs<D> &lo, cons
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
+    // Lazy rescaling: the running maximum is only a reference point (any value cancels in the
+    // final normalisation), so it is moved, and the accumulators rescaled, only when some query's
+    // maximum has grown by more than 2^8; until then the probabilities may exceed 1 by that factor.
     const float m_new = fmaxf(m_run, xhalf_max(mx));
-    if (__any(m_new > m_run)) {
+    if (__any((m_new - m_run) * c > 8.f)) {
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
         l_run *= alpha;
 #pragma unroll
