@@ -632,38 +632,43 @@ __device__ __forceinline__ void score_valu(const float *stats, f32x16 &sacc, f32
     }
 }
 
-// One steady-state step of a score wave: the matrix half of the next tile
-// (accumulators s_nxt, dp_nxt; tile at the offsets lo_n, statistics stats_n)
-// written out between the vector half of the current one (s_cur, dp_cur,
-// stats_c). The order below is the order of issue: scheduling barriers keep
-// the compiler from regrouping it into a matrix phase and a vector phase,
-// which would leave the matrix pipe idle for the whole vector phase.
-template <int D, int QOFF, int DOOFF>
-__device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &lo_n, const float *stats_n,
-                                           const float *stats_c, const bf16x8 *kf, const bf16x8 *nvf, f32x16 &s_nxt,
-                                           f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, char *pds, float c, int lane) {
-    constexpr int KS = D / 16;
-    constexpr int PRE = 8;                         // vector elements done while the tile reads are in flight
-    constexpr int EPS = (16 - PRE) / KS;           // ... per contraction step after that
-    static_assert(PRE + EPS * KS == 16, "vector elements must divide evenly over the contraction steps");
-    const int half = lane >> 5;
-    bf16x8 qa[KS], da[KS];
+// Steady state of a score wave. Everything a step needs from LDS is read at the
+// end of the step before (ScoreIn: the Q / dO fragments of the tile whose matrix
+// half comes next, the lse2 of the tile whose vector half comes next; delta goes
+// straight into the accumulator that matrix half will add to), so after the
+// barrier the matrix instructions start at once. score_step writes the matrix
+// half of the next tile (s_nxt, dp_nxt) out between the vector half of the
+// current one (s_cur, dp_cur); the order below is the order of issue:
+// scheduling barriers keep the compiler from regrouping it into a matrix phase
+// and a vector phase, which would leave the matrix pipe idle meanwhile.
+template <int D> struct ScoreIn {
+    bf16x8 qa[D / 16], da[D / 16];
     f32x4 l4[4];
+};
+template <int D, int QOFF, int DOOFF>
+__device__ __forceinline__ void score_load(const char *smem, const LaneOffs<D> &lo_m, const float *stats_m,
+                                           const float *stats_v, ScoreIn<D> &in, f32x16 &dp_init, int lane) {
+    const int half = lane >> 5;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) l4[g] = *reinterpret_cast<const f32x4 *>(stats_c + g * 16 + half * 4);
+    for (int g = 0; g < 4; ++g) in.l4[g] = *reinterpret_cast<const f32x4 *>(stats_v + g * 16 + half * 4);
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        qa[s] = lo_n.template frag<QOFF>(smem, s);
-        da[s] = lo_n.template frag<DOOFF>(smem, s);
+    for (int s = 0; s < D / 16; ++s) {
+        in.qa[s] = lo_m.template frag<QOFF>(smem, s);
+        in.da[s] = lo_m.template frag<DOOFF>(smem, s);
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(stats_n + g * 16 + 8 + half * 4);
+        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(stats_m + g * 16 + 8 + half * 4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) dp_nxt[4 * g + e] = d4[e];
+        for (int e = 0; e < 4; ++e) dp_init[4 * g + e] = d4[e];
     }
+}
+template <int D>
+__device__ __forceinline__ void score_step(const ScoreIn<D> &in, const bf16x8 *kf, const bf16x8 *nvf, f32x16 &s_nxt,
+                                           f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, char *pds, float c) {
+    constexpr int KS = D / 16, EPS = 16 / KS;      // vector elements per contraction step
     auto vec = [&](int i) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s_cur[i], c, -l4[i >> 2][i & 3]));
+        const float p = __builtin_amdgcn_exp2f(fmaf(s_cur[i], c, -in.l4[i >> 2][i & 3]));
         s_cur[i] = p;
         dp_cur[i] *= p;
     };
@@ -673,15 +678,12 @@ __device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &
     };
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < PRE; ++i) vec(i);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
     for (int s = 0; s < KS; ++s) {
-        s_nxt = mfma32(qa[s], kf[s], s == 0 ? zero16() : s_nxt);
-        dp_nxt = mfma32(da[s], nvf[s], dp_nxt);
-        if (s == 0) emit(0);
+        s_nxt = mfma32(in.qa[s], kf[s], s == 0 ? zero16() : s_nxt);
+        dp_nxt = mfma32(in.da[s], nvf[s], dp_nxt);
 #pragma unroll
-        for (int i = PRE + s * EPS; i < PRE + (s + 1) * EPS; ++i) vec(i);
+        for (int i = s * EPS; i < (s + 1) * EPS; ++i) vec(i);
+        if ((s + 1) * EPS == 8) emit(0);
         __builtin_amdgcn_sched_barrier(0);
     }
     emit(1);
@@ -797,28 +799,34 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
         };
         if (fused) {
             // two accumulator sets take turns: while one goes through the vector half, the
-            // matrix half of the next tile fills the other (no copies: the loop body is two steps)
+            // matrix half of the next tile fills the other (no copies: the loop body is two steps).
+            // At the top of step t (t even) set A holds S / delta - dP of tile t, `in` the
+            // fragments of tile t+1 and the lse2 of tile t, and dpB starts at the delta of tile t+1.
             f32x16 sA, dpA, sB, dpB;
-            auto both = [&](f32x16 &s_nxt, f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, int st, int stn, int buf) {
-                score_step<D, 0, TB>(smem, at_stage(stn), stats_s[stn], stats_s[st], kf, nvf, s_nxt, dp_nxt, s_cur,
-                                     dp_cur, pds + (buf << 14), c, lane);
-                wait_lgkm0();   // P / dS are in LDS before the next barrier publishes them
+            ScoreIn<D> in;
+            auto load_in = [&](int st_m, int st_v, f32x16 &dp_init) {
+                score_load<D, 0, TB>(smem, at_stage(st_m), stats_s[st_m], stats_s[st_v], in, dp_init, lane);
+                wait_lgkm0();   // P / dS are in LDS before the next barrier publishes them; the reads are done too
             };
-            step_barrier();                                           // step -1
+            step_barrier();                                           // step -1: tiles 0 and 1 have landed
             score_mfma<D, 0, TB>(smem, at_stage(0), stats_s[0], kf, nvf, sA, dpA, lane);
-            int st = 0, t = 0;      // st = stage of tile t; set A holds tile t (t even)
+            load_in(ntiles > 1 ? 1 : 0, 0, dpB);
+            int st = 0, t = 0;      // st = stage of tile t
             for (; t + 2 < ntiles; t += 2) {
-                const int st1 = next_stage(st), st2 = next_stage(st1);
-                step_barrier();                                       // step t
-                both(sB, dpB, sA, dpA, st, st1, 0);
+                const int st1 = next_stage(st), st2 = next_stage(st1), st3 = next_stage(st2);
+                step_barrier();                                       // step t: tile t+2 has landed
+                score_step<D>(in, kf, nvf, sB, dpB, sA, dpA, pds, c);
+                load_in(st2, st1, dpA);
                 step_barrier();                                       // step t + 1
-                both(sA, dpA, sB, dpB, st1, st2, 1);
+                score_step<D>(in, kf, nvf, sA, dpA, sB, dpB, pds + (1 << 14), c);
+                load_in(t + 3 < ntiles ? st3 : st2, st2, dpB);
                 st = st2;
             }
             if (t + 1 < ntiles) {                                     // two tiles left
                 const int st1 = next_stage(st);
                 step_barrier();
-                both(sB, dpB, sA, dpA, st, st1, 0);
+                score_step<D>(in, kf, nvf, sB, dpB, sA, dpA, pds, c);
+                wait_lgkm0();
                 step_barrier();
                 score_valu(stats_s[st1], sB, dpB, pds + (1 << 14), c, lane);
             } else {                                                  // one tile left
@@ -935,16 +943,17 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
         };
         // own copies of tile u landed: at most the copies of the younger tiles may be outstanding
         auto wait_tile = [&](int u) {
-            const int younger = min(NS - 4, ntiles - 1 - u);
-            static_assert(NS - 4 <= 4 && 4 * LPT < 64, "cases below");
-            if (younger >= 4) wait_vmcnt<(NS - 4 >= 4 ? 4 : 0) * LPT>();
-            else if (younger == 3) wait_vmcnt<(NS - 4 >= 3 ? 3 : 0) * LPT>();
-            else if (younger == 2) wait_vmcnt<(NS - 4 >= 2 ? 2 : 0) * LPT>();
+            const int younger = min(NS - 5, ntiles - 1 - u);
+            static_assert(NS - 5 >= 1 && NS - 5 <= 4 && 4 * LPT < 64, "cases below");
+            if (younger >= 4) wait_vmcnt<(NS - 5 >= 4 ? 4 : 0) * LPT>();
+            else if (younger == 3) wait_vmcnt<(NS - 5 >= 3 ? 3 : 0) * LPT>();
+            else if (younger == 2) wait_vmcnt<(NS - 5 >= 2 ? 2 : 0) * LPT>();
             else if (younger == 1) wait_vmcnt<LPT>();
             else wait_vmcnt<0>();
         };
+        // the barrier of step t publishes tile t+2 (the score waves read it at the end of step t)
         auto step_wait = [&](int t) {
-            if (t + 1 < ntiles) wait_tile(t + 1);
+            if (t < ntiles) wait_tile(min(t + 2, ntiles - 1));
             step_barrier();
         };
         auto step_issue = [&](int t) {
