@@ -719,6 +719,8 @@ template <int D>
 __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
     typedef bf16_t T;
     constexpr int BQ = 32, NS = 7;
+    constexpr int kWide = 3;                       // query tiles per step of a single-key-block item
+    static_assert(2 * kWide <= NS && kWide <= 4, "two alternating sets of stages, one P / dS slot per score wave");
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int TB = BQ * D * 2;                 // bytes of one Q (or dO) tile
     constexpr int SB = 2 * TB;                     // bytes of one stage: Q tile, dO tile
@@ -836,6 +838,19 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
             wait_lgkm0();
             step_barrier();                                           // step ntiles
             step_barrier();                                           // step ntiles + 1 (the gradient waves' last)
+        } else if (split) {
+            // a single key block: kWide query tiles per step, one per score wave (see the grad waves)
+            for (int k = 0; k * kWide < ntiles; ++k) {
+                step_barrier();                                       // the tiles of step k have landed
+                if (w4 < kWide && k * kWide + w4 < ntiles) {
+                    const int st = (k & 1) * kWide + w4;
+                    f32x16 sacc, dpacc;
+                    score_mfma<D, 0, TB>(smem, at_stage(st), stats_s[st], kf, nvf, sacc, dpacc, lane);
+                    score_valu(stats_s[st], sacc, dpacc, pds + ((k & 1) << 14), c, lane);
+                    wait_lgkm0();
+                }
+                step_barrier();                                       // P / dS of step k are in LDS
+            }
         } else {
             int st = NS - 1;     // stage of tile t
             for (int t = -1; t <= ntiles + 1; ++t) {
@@ -965,9 +980,11 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
             for (int v = 0; v < 4; ++v) issue_words(v);
             wait_vmcnt<0>();
         }
+        if (!split) {
 #pragma unroll
-        for (int p = 0; p <= NS - 4; ++p)
-            if (p < ntiles) issue_group(p);
+            for (int p = 0; p <= NS - 4; ++p)
+                if (p < ntiles) issue_group(p);
+        }
 
         // ---- matrix work. A grad wave owns one block of 32 features (rows of dK^T / dV^T) for
         // KPW key blocks: the transposed Q / dO fragments it reads from a tile are then shared by
@@ -1024,6 +1041,39 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
             dv[j] = mfma32(f.dot[1], P[1], dv[j]);
             dk[j] = mfma32(f.qt[1], P[3], dk[j]);
         };
+        if (split) {
+            // A tile of <= 32 keys (the ragged tail of a chunk) is one key block: per step each of
+            // kWide score waves takes a query tile of its own and the grad waves multiply all of
+            // them, so a step still carries a full load of matrix work. Two sets of kWide stages
+            // alternate; two barriers per step (tiles landed, P / dS written), no deeper pipeline.
+            ist = 0;
+#pragma unroll
+            for (int i = 0; i < kWide; ++i)
+                if (i < ntiles) issue_group(i);
+            for (int k = 0; k * kWide < ntiles; ++k) {
+                wait_vmcnt<0>();
+                step_barrier();                                       // the tiles of step k have landed
+                ist = ((k + 1) & 1) * kWide;
+#pragma unroll
+                for (int i = 0; i < kWide; ++i)
+                    if ((k + 1) * kWide + i < ntiles) issue_group((k + 1) * kWide + i);
+                TFrags f[kWide];
+#pragma unroll
+                for (int i = 0; i < kWide; ++i) f[i] = tload((k & 1) * kWide + min(i, ntiles - 1 - k * kWide));
+                step_barrier();                                       // P / dS of step k are in LDS
+                if (nmine > 0) {
+#pragma unroll
+                    for (int i = 0; i < kWide; ++i)
+                        if (k * kWide + i < ntiles) {
+                            const char *pp = pds_rd + ((k & 1) << 14) + i * 4096;
+                            bf16x8 P[4];
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) P[x] = *reinterpret_cast<const bf16x8 *>(pp + x * 1024);
+                            gmfma(f[i], P, 0);
+                        }
+                }
+            }
+        } else {
         step_wait(-1);
         step_issue(-1);
         step_wait(0);
@@ -1077,6 +1127,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
                     wait_lgkm0();
                 }
             }
+        }
         }
 
         // ---- results: lane = key, registers = the wave's 32 features; the accumulator holds -dK
