@@ -12,7 +12,7 @@ namespace moc {
 
 constexpr int kBM = 128;         // queries per workgroup in the query-stationary passes
 constexpr int kKeyTile = 128;    // keys per workgroup in the key-stationary pass (4 waves x 32)
-constexpr int kTextSeg = 4096;   // queries per partial of a text key tile in the key-stationary pass
+constexpr int kTextSeg = 8192;   // queries per partial of a text key tile in the key-stationary pass
 
 // One query tile of the forced-link pass: queries [q_start, q_start+q_count)
 // all belong to window `win` and share its key ranges.
