@@ -11,14 +11,14 @@
 // tile each); the [N, C] score matrix never exists in memory.
 //
 // Per-lane top-k without a sort and without paying wave divergence per score:
-//   pass 1  per lane, the top-k of the TILE MAXIMA (values only, a min/max
-//           network): its k-th entry is a lower bound tau of the k-th best score;
-//   pass 2  scores are recomputed (cheap on matrix cores), those >= tau (few)
-//           are appended to a per-lane queue in LDS;
-//   drain   the queue is inserted into a register-resident sorted list with
-//           strict comparisons, in chunk order, so ties keep the lower index;
+//   filter  scores >= tau, the lane's k-th best so far (-inf-like until k scores
+//           have been seen), are appended to a per-lane queue in LDS: after the
+//           first tiles only a few per tile pass;
+//   drain   when a queue would overflow (and at the end) it is inserted into a
+//           register-resident sorted list with strict comparisons, in chunk
+//           order, so ties keep the lower index; tau rises to the new k-th best;
 //   merge   the two half-waves exchange their lists.
-// A full queue is drained on the spot, so any data (ties, few tiles) stays exact.
+// One pass over the chunks; any data (ties, few tiles) stays exact.
 #include "moc_attn_common.h"
 
 namespace moc {
@@ -175,40 +175,9 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
         return acc;
     };
 
-    // ---------------- pass 1: per-lane top-k of tile maxima -> lower bound tau
-    // right-aligned value list: [KMAX-topk, KMAX) descending, the rest +inf
-    float tv[KMAX];
+    // ---------------- collect scores >= tau (the k-th best so far), keep an exact sorted list
     const int base = KMAX - topk;
-#pragma unroll
-    for (int p = 0; p < KMAX; ++p) tv[p] = (p >= base) ? -INFINITY : INFINITY;
-    auto pass1 = [&](auto cur, int t) {
-        constexpr int CUR = decltype(cur)::value;
-        const bool more = t + 1 < ntiles;
-        if (more) issue(t + 1, CUR ^ 1);
-        const f32x16 sc = scores(cur, t);
-        float x = sc[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) x = fmaxf(x, sc[r]);
-#pragma unroll
-        for (int p = 0; p < KMAX; ++p) {
-            const float hi = fmaxf(tv[p], x);
-            x = fminf(tv[p], x);
-            tv[p] = hi;
-        }
-        if (more) { ld.commit(nullptr); __syncthreads(); }
-        return more;
-    };
-    issue(0, 0);
-    ld.commit(nullptr);
-    __syncthreads();
-    for (int t = 0;;) {
-        if (!pass1(IC<0>{}, t++)) break;
-        if (!pass1(IC<1>{}, t++)) break;
-    }
-    // both half-waves hold a valid bound for the query; never let -inf pass the filter
-    float tau = fmaxf(xhalf_max(tv[KMAX - 1]), -3.0e38f);
-
-    // ---------------- pass 2: collect scores >= tau, keep an exact sorted list
+    float tau = -3.0e38f;      // never let -inf (an ineligible chunk) pass the filter
     float val[KMAX];
     int idx[KMAX];
 #pragma unroll
@@ -227,7 +196,7 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
         cnt = 0;
         tau = fmaxf(tau, val[KMAX - 1]);     // once the list is full its tail bounds the k-th best
     };
-    auto pass2 = [&](auto cur, int t) {
+    auto scan = [&](auto cur, int t) {
         constexpr int CUR = decltype(cur)::value;
         const bool more = t + 1 < ntiles;
         if (more) issue(t + 1, CUR ^ 1);
@@ -253,8 +222,8 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
     ld.commit(nullptr);
     __syncthreads();
     for (int t = 0;;) {
-        if (!pass2(IC<0>{}, t++)) break;
-        if (!pass2(IC<1>{}, t++)) break;
+        if (!scan(IC<0>{}, t++)) break;
+        if (!scan(IC<1>{}, t++)) break;
     }
     drain();
 
