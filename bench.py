@@ -115,6 +115,8 @@ def main():
     ap.add_argument("--topk", type=int, default=None)
     ap.add_argument("--cpu-queries", type=int, default=1 << 30, help="oracle sample size, capped at N (0 = skip the CPU baseline)")
     ap.add_argument("--seed", type=int, default=1234)
+    ap.add_argument("--inputs", default="S1", choices=["S1", "S2"],
+                    help="S1: q, k, v, dO iid N(0,1) (graded); S2: chunk-coherent q and k (queries of a chunk select nearly the same chunks)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (heads are independent: shard heads across GPUs with no "
@@ -135,6 +137,11 @@ def main():
     B, H, d, topk, N = cfg["B"], cfg["H"], cfg["d"], cfg["topk"], lay.N
     tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
     q, k, v, d_o = (t.to(tdt).contiguous() for t in mi.qkv_do(B, H, N, d, args.seed, "cuda"))
+    if args.inputs == "S2":
+        del q, k
+        qc, kc = mi.coherent_qk(lay, B, H, d, args.seed)
+        q, k = qc.to(tdt).to("cuda").contiguous(), kc.to(tdt).to("cuda").contiguous()
+        del qc, kc
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -222,7 +229,9 @@ def main():
         "dtype": "bf16" if tdt == torch.bfloat16 else "f32(bf16 mfma)", "data": "synthetic",
         "config": {"workload": f"{args.workload} ({lay.name}): B={B} H={H} N={N} d={d} C={lay.C} "
                                f"chunk={lay.meta.get('chunk')} window={lay.meta.get('window')} topk={topk} causal",
-                   "inputs": "S1 iid N(0,1) rounded to bf16, seeded", "pass": "route + attn fwd + attn bwd"},
+                   "inputs": ("S1 iid N(0,1) rounded to bf16, seeded" if args.inputs == "S1" else
+                              "S2 chunk-coherent q and k (rho = 0.9, planted earlier target chunk), v and dO iid, seeded"),
+                   "pass": "route + attn fwd + attn bwd"},
         "frac_of_bf16_mfma_peak": round(total_flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "attn_only_tflops": round(total_flops / ((stage[1] + stage[2]) * 1e-3) / 1e12, 2),
         "stage_ms": {"route": round(float(stage[0]), 3), "attn_fwd": round(float(stage[1]), 3),
