@@ -110,9 +110,9 @@ template <int BN> struct TileIter {
     }
 };
 
-// Stages ROWS source rows of D features into a row-major LDS tile
-// (RowTile<D>), 16 bytes per lane and pass, through registers so the global
-// loads of the next tile overlap the math on the current one.
+// Stages ROWS source rows of D features into a swizzled LDS tile (SwTile<D>),
+// 16 bytes per lane and pass, through registers (conversion to bf16 on the way)
+// so the global loads of the next tile overlap the math on the current one.
 // rowfn(r) gives the global row of tile row r (clamped by the caller).
 template <int D, typename T, int ROWS> struct RowStager {
     static constexpr int CG = D / 8, RPP = 256 / CG, P = (ROWS + RPP - 1) / RPP;
@@ -129,15 +129,6 @@ template <int D, typename T, int ROWS> struct RowStager {
     __device__ __forceinline__ void load(const T *base, int start, int valid) {
         load_fn(base, [=](int r) { return start + min(r, valid - 1); });
     }
-    __device__ __forceinline__ void store(bf16_t *lds) const {
-#pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const int row = rr + p * RPP;
-            if (ROWS % RPP == 0 || row < ROWS)
-                *reinterpret_cast<u32x4 *>(lds + row * RowTile<D>::kStride + cg * 8) = __builtin_bit_cast(u32x4, reg[p]);
-        }
-    }
-    // same rows into a swizzled tile (SwTile<D>)
     __device__ __forceinline__ void store_sw(bf16_t *lds) const {
 #pragma unroll
         for (int p = 0; p < P; ++p) {
@@ -195,19 +186,16 @@ __device__ __forceinline__ void store_rows_bf16(char *smem, int wave, int lane, 
 // of LDS, lane l writing bytes [16 l, 16 l + 16), so each lane fetches the
 // global element that belongs at its swizzled LDS position.
 // fp32 storage needs a conversion, so it goes through registers.
-template <int D, typename T, int ROWS, int NW = 4> struct TileLoader;   // NW = waves that share the loads
+template <int D, typename T, int ROWS> struct TileLoader;
 
-template <int D, int ROWS, int NW> struct TileLoader<D, bf16_t, ROWS, NW> {
+template <int D, int ROWS> struct TileLoader<D, bf16_t, ROWS> {
+    static constexpr int NW = 4;                        // waves of the workgroup that share the loads
     static constexpr int RPI = 512 / D;                 // rows per wave instruction
     static constexpr int NI = ROWS / RPI;               // wave instructions per tile
     static constexpr int P = (NI + NW - 1) / NW;        // per wave
-    // With fewer instructions than waves the surplus waves repeat the loads of the
-    // first ones (same source, same destination): every wave then issues the same
-    // number of loads per tile, which is what a bounded vmcnt wait counts on.
-    static constexpr bool kRepeat = NI < NW;
-    static_assert(kRepeat ? NW % NI == 0 : NI % NW == 0, "tile rows must divide evenly among the waves");
+    static_assert(NI % NW == 0, "tile rows must divide evenly among the waves");
     int wave, rlo, cgp;
-    __device__ __forceinline__ int slot(int p) const { return kRepeat ? wave % NI : wave + NW * p; }
+    __device__ __forceinline__ int slot(int p) const { return wave + NW * p; }
     __device__ __forceinline__ explicit TileLoader(int tid)
         : wave(__builtin_amdgcn_readfirstlane(tid >> 6)), rlo((tid & 63) / (D / 8)), cgp((tid & 63) % (D / 8)) {}
     static __device__ __forceinline__ void dma(const bf16_t *g, bf16_t *lds) { async_copy16(g, lds); }
@@ -219,119 +207,6 @@ template <int D, int ROWS, int NW> struct TileLoader<D, bf16_t, ROWS, NW> {
             const int row = n * RPI + rlo;
             const int cg = cgp ^ SwTile<D>::sw(row);
             dma(base + (size_t)rowfn(row) * D + cg * 8, lds + n * 512);
-        }
-    }
-    // Gathered rows named by a wave-uniform list (entries = (row << 5) | slot).
-    // The list is read through scalar loads, which do not touch the vector-memory
-    // counter that the asynchronous tile loads are tracked with. ListRows holds
-    // this wave's rows of one tile; load it once, use it for every tensor.
-    // The loads and the wait for them are ONE asm statement: the compiler does
-    // not know that a scalar load completes later, so the results must be valid
-    // when the statement ends (outputs are early-clobber: the address registers
-    // of the later loads must stay intact while the earlier ones issue).
-    struct ListRows { int row[P]; };
-    // The same in two steps, for callers that want the list words a step ahead of
-    // the copies that use them: fetch_list() reads this wave's words of a tile with
-    // ordinary loads from the constant address space (wave-uniform address, so they
-    // are scalar loads the compiler tracks itself), select_rows() turns them into
-    // the lane's row once they are needed. Only for one instruction per wave (P == 1).
-    struct ListRaw { int last; int e[RPI]; };
-    __device__ __forceinline__ ListRaw fetch_list(const int32_t *entries, int valid) const {
-        static_assert(P == 1, "one wave instruction per tile");
-        typedef const __attribute__((address_space(4))) int32_t *cptr;
-        cptr c = (cptr)(uintptr_t)entries;
-        ListRaw r;
-        r.last = c[valid - 1];
-        const int n = slot(0);
-#pragma unroll
-        for (int j = 0; j < RPI; ++j) r.e[j] = c[n * RPI + j];
-        return r;
-    }
-    __device__ __forceinline__ ListRows select_rows(const ListRaw &raw, int valid) const {
-        const int n = slot(0);
-        int e = raw.last;
-#pragma unroll
-        for (int j = 0; j < RPI; ++j) {
-            const int ej = n * RPI + j < valid ? raw.e[j] : raw.last;
-            e = rlo == j ? ej : e;
-        }
-        ListRows r;
-        r.row[0] = e >> 5;
-        return r;
-    }
-    __device__ __forceinline__ ListRows list_rows(const int32_t *entries, int valid) const {
-        typedef int i32x4 __attribute__((ext_vector_type(4)));
-        static_assert(RPI == 4 || RPI == 8, "rows per instruction");
-        static_assert(P <= 4, "at most four wave instructions per tile and wave");
-        constexpr int NV = RPI / 4;
-        i32x4 ev[4][2];
-        int last;                                  // rows >= valid repeat the last valid row
-        const int32_t *p0 = entries + (valid - 1);
-        const int32_t *pv[4];
-#pragma unroll
-        for (int p = 0; p < 4; ++p) pv[p] = entries + (p < P ? slot(p) : slot(P - 1)) * RPI;
-        if (P == 1 && NV == 1) {
-            asm volatile("s_load_dword %0, %2, 0x0\n"
-                         "s_load_dwordx4 %1, %3, 0x0\n"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&s"(last), "=&s"(ev[0][0])
-                         : "s"(p0), "s"(pv[0])
-                         : "memory");
-        } else if (P == 1) {
-            asm volatile("s_load_dword %0, %3, 0x0\n"
-                         "s_load_dwordx4 %1, %4, 0x0\n"
-                         "s_load_dwordx4 %2, %4, 0x10\n"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&s"(last), "=&s"(ev[0][0]), "=&s"(ev[0][1])
-                         : "s"(p0), "s"(pv[0])
-                         : "memory");
-        } else if (NV == 1) {
-            asm volatile("s_load_dword %0, %5, 0x0\n"
-                         "s_load_dwordx4 %1, %6, 0x0\n"
-                         "s_load_dwordx4 %2, %7, 0x0\n"
-                         "s_load_dwordx4 %3, %8, 0x0\n"
-                         "s_load_dwordx4 %4, %9, 0x0\n"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&s"(last), "=&s"(ev[0][0]), "=&s"(ev[1][0]), "=&s"(ev[2][0]), "=&s"(ev[3][0])
-                         : "s"(p0), "s"(pv[0]), "s"(pv[1]), "s"(pv[2]), "s"(pv[3])
-                         : "memory");
-        } else {
-            asm volatile("s_load_dword %0, %9, 0x0\n"
-                         "s_load_dwordx4 %1, %10, 0x0\n"
-                         "s_load_dwordx4 %2, %10, 0x10\n"
-                         "s_load_dwordx4 %3, %11, 0x0\n"
-                         "s_load_dwordx4 %4, %11, 0x10\n"
-                         "s_load_dwordx4 %5, %12, 0x0\n"
-                         "s_load_dwordx4 %6, %12, 0x10\n"
-                         "s_load_dwordx4 %7, %13, 0x0\n"
-                         "s_load_dwordx4 %8, %13, 0x10\n"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&s"(last), "=&s"(ev[0][0]), "=&s"(ev[0][1]), "=&s"(ev[1][0]), "=&s"(ev[1][1]),
-                           "=&s"(ev[2][0]), "=&s"(ev[2][1]), "=&s"(ev[3][0]), "=&s"(ev[3][1])
-                         : "s"(p0), "s"(pv[0]), "s"(pv[1]), "s"(pv[2]), "s"(pv[3])
-                         : "memory");
-        }
-        ListRows r;
-#pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const int n = slot(p);
-            int e = last;
-#pragma unroll
-            for (int j = 0; j < RPI; ++j) {
-                const int ej = n * RPI + j < valid ? ev[p][j / 4][j % 4] : last;
-                e = rlo == j ? ej : e;
-            }
-            r.row[p] = e >> 5;
-        }
-        return r;
-    }
-    __device__ __forceinline__ void issue_list(const bf16_t *base, const ListRows &lr, bf16_t *lds) const {
-#pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const int n = slot(p);
-            const int row = n * RPI + rlo;
-            const int cg = cgp ^ SwTile<D>::sw(row);
-            dma(base + (size_t)lr.row[p] * D + cg * 8, lds + n * 512);
         }
     }
     // contiguous rows [0, valid) of a tile whose first row is at `tile` (a
@@ -350,7 +225,7 @@ template <int D, int ROWS, int NW> struct TileLoader<D, bf16_t, ROWS, NW> {
     __device__ __forceinline__ void commit(bf16_t *) const { wait_vmcnt<0>(); }
 };
 
-template <int D, int ROWS> struct TileLoader<D, float, ROWS, 4> {
+template <int D, int ROWS> struct TileLoader<D, float, ROWS> {
     RowStager<D, float, ROWS> st;
     __device__ __forceinline__ explicit TileLoader(int tid) : st(tid) {}
     template <typename F> __device__ __forceinline__ void issue(const float *base, F rowfn, bf16_t *) {
@@ -360,47 +235,6 @@ template <int D, int ROWS> struct TileLoader<D, float, ROWS, 4> {
         st.load_fn(tile, [=](int r) { return min(r, valid - 1); });
     }
     __device__ __forceinline__ void commit(bf16_t *lds) const { st.store_sw(lds); }
-};
-
-// Stages COLS source rows transposed into ColTile<COLS> ([D][COLS+4]): a lane
-// loads 8 features of 4 consecutive source rows and writes eight 8-byte
-// column pieces. The lane -> (row group, feature group) map keeps the writes
-// of each 32-lane phase on distinct banks. `wv` is the wave's index among the
-// waves that take part; lanes with no unit do nothing (active == false).
-template <int D, typename T, int COLS> struct ColStager {
-    static constexpr int A = COLS / 4, G = D / 8;
-    static_assert(A == 16 || A == 8, "COLS must be 64 or 32");
-    int a, g;
-    bool active;
-    bf16x8 reg[4];
-    __device__ __forceinline__ ColStager(int lane, int wv) {
-        if (A == 16) {
-            const int gs = lane >> 4;
-            a = lane & 15;
-            g = (((gs & 1) << 1) | (gs >> 1)) + 4 * wv;
-        } else {
-            a = lane & 7;
-            g = (lane >> 3) + 8 * wv;
-        }
-        active = g < G && wv >= 0;
-    }
-    __device__ __forceinline__ explicit ColStager(int tid) : ColStager(tid & 63, tid >> 6) {}
-    template <typename F> __device__ __forceinline__ void load_fn(const T *base, F rowfn) {
-        if (!active) return;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) reg[kk] = Io<T>::load8(base + (size_t)rowfn(4 * a + kk) * D + g * 8);
-    }
-    __device__ __forceinline__ void load(const T *base, int start, int valid) {
-        load_fn(base, [=](int r) { return start + min(r, valid - 1); });
-    }
-    __device__ __forceinline__ void store(bf16_t *lds) const {
-        if (!active) return;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            bf16x4 t = {reg[0][e], reg[1][e], reg[2][e], reg[3][e]};
-            *reinterpret_cast<u32x2 *>(lds + (8 * g + e) * ColTile<COLS>::kStride + 4 * a) = __builtin_bit_cast(u32x2, t);
-        }
-    }
 };
 
 }  // namespace moc

@@ -108,32 +108,6 @@ template <> struct Io<float> {
 // exchange with the other half-wave (lane ^ 32)
 __device__ __forceinline__ float xhalf(float v) { return __shfl_xor(v, 32, 64); }
 
-// Row-major LDS tile [ROWS][D + 8] of bf16 (row stride (D+8)*2 bytes keeps the
-// 16-byte operand reads of 16 consecutive rows on distinct banks).
-template <int D> struct RowTile {
-    static constexpr int kStride = D + 8;
-    // operand fragment: row r, contraction elements [16*step + 8*half, +8)
-    static __device__ __forceinline__ bf16x8 frag(const bf16_t *base, int r, int step, int half) {
-        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(base + r * kStride + step * 16 + half * 8));
-    }
-};
-
-// Transposed LDS tile [D][COLS + 4]: element (x, c) = source row c, feature x.
-// Row stride (COLS+4)*2 bytes: the 8-byte reads of 32 consecutive feature rows
-// fall on distinct bank pairs when COLS is a multiple of 64.
-template <int COLS> struct ColTile {
-    static constexpr int kStride = COLS + 4;
-    // operand fragment for contraction step s (16 source rows) in the permuted
-    // order of acc_to_frag: slots 0..3 -> rows 16s + 4h + {0..3}, slots 4..7 -> +8.
-    static __device__ __forceinline__ bf16x8 frag(const bf16_t *base, int x, int s, int half) {
-        const bf16_t *p = base + x * kStride + 16 * s + 4 * half;
-        u32x2 a = *reinterpret_cast<const u32x2 *>(p);
-        u32x2 b = *reinterpret_cast<const u32x2 *>(p + 8);
-        u32x4 r = {a[0], a[1], b[0], b[1]};
-        return __builtin_bit_cast(bf16x8, r);
-    }
-};
-
 // Row-major LDS tile [ROWS][D] of bf16 without padding; the 16-byte column
 // groups of a row are XOR-swizzled by the row index so that BOTH access
 // patterns below are bank-conflict free:
@@ -267,10 +241,6 @@ __device__ __forceinline__ void async_copy4_at(const void *g, uint32_t lds) {
 __device__ __forceinline__ void async_copy4_at(const void *base, uint32_t off, uint32_t lds) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                  :: "v"(off), "s"(uniform_ptr(base)), "s"(__builtin_amdgcn_readfirstlane(lds)) : "memory", "m0");
-}
-__device__ __forceinline__ void async_copy4(const void *g, void *lds) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-                 :: "v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_address(lds))) : "memory", "m0");
 }
 
 // max (or sum) of a value with its counterpart in the other half-wave, in all
