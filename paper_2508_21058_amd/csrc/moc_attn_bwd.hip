@@ -663,10 +663,19 @@ __device__ __forceinline__ void score_load(const char *smem, const LaneOffs<D> &
         for (int e = 0; e < 4; ++e) dp_init[4 * g + e] = d4[e];
     }
 }
-template <int D>
-__device__ __forceinline__ void score_step(const ScoreIn<D> &in, const bf16x8 *kf, const bf16x8 *nvf, f32x16 &s_nxt,
-                                           f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, char *pds, float c) {
+// One steady-state step. The fragments a contraction step has consumed are refilled from the
+// next tile (at the offsets lo_m) right behind it; the rest of the next step's operands (last
+// fragments, lse2 from stats_v, delta from stats_m into dp_cur, which is free once its P / dS
+// are emitted) follow the last P / dS write. On return at most kScoreTail LDS reads are
+// younger than that write: wait_lgkm<kScoreTail>() before the barrier that publishes P / dS.
+constexpr int kScoreTail = 10;
+template <int D, int QOFF, int DOOFF>
+__device__ __forceinline__ void score_step(const char *smem, const LaneOffs<D> &lo_m, const float *stats_m,
+                                           const float *stats_v, ScoreIn<D> &in, const bf16x8 *kf, const bf16x8 *nvf,
+                                           f32x16 &s_nxt, f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, char *pds,
+                                           float c, int lane) {
     constexpr int KS = D / 16, EPS = 16 / KS;      // vector elements per contraction step
+    const int half = lane >> 5;
     auto vec = [&](int i) {
         const float p = __builtin_amdgcn_exp2f(fmaf(s_cur[i], c, -in.l4[i >> 2][i & 3]));
         s_cur[i] = p;
@@ -685,8 +694,25 @@ __device__ __forceinline__ void score_step(const ScoreIn<D> &in, const bf16x8 *k
         for (int i = s * EPS; i < (s + 1) * EPS; ++i) vec(i);
         if ((s + 1) * EPS == 8) emit(0);
         __builtin_amdgcn_sched_barrier(0);
+        if (s >= 1) {
+            in.qa[s - 1] = lo_m.template frag<QOFF>(smem, s - 1);
+            in.da[s - 1] = lo_m.template frag<DOOFF>(smem, s - 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
     emit(1);
+    __builtin_amdgcn_sched_barrier(0);
+    in.qa[KS - 1] = lo_m.template frag<QOFF>(smem, KS - 1);
+    in.da[KS - 1] = lo_m.template frag<DOOFF>(smem, KS - 1);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) in.l4[g] = *reinterpret_cast<const f32x4 *>(stats_v + g * 16 + half * 4);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(stats_m + g * 16 + 8 + half * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dp_cur[4 * g + e] = d4[e];
+    }
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 // bf16 storage. Eight waves per workgroup, two per SIMD, in two roles: waves
@@ -792,11 +818,18 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
             nvf[s] = __builtin_bit_cast(bf16x8, v);
         }
         const float c = a.scale_log2;
-        auto at_stage = [&](int st) {      // row-operand offsets of a stage (too far apart for an instruction offset)
-            lo.pin();
+        // Row-operand offsets of a stage (stages are too far apart for an instruction offset). The
+        // swizzle is an XOR of the 16-byte group index, and the groups of contraction step s are 2s
+        // and 2s+1, so the eight offsets of a lane differ from the first one by XOR with 32 s: one
+        // register is kept, the rest is rebuilt where needed (the empty asm keeps the rebuilt values
+        // from being hoisted into eight long-lived registers).
+        int row0 = lo.row[0];
+        auto at_stage = [&](int st) {
+            asm volatile("" : "+v"(row0));
             LaneOffs<D> lc;
+            const int b = row0 + st * SB;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) lc.row[s] = lo.row[s] + st * SB;
+            for (int s = 0; s < KS; ++s) lc.row[s] = b ^ (32 * s);
             return lc;
         };
         if (fused) {
@@ -813,21 +846,26 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
             step_barrier();                                           // step -1: tiles 0 and 1 have landed
             score_mfma<D, 0, TB>(smem, at_stage(0), stats_s[0], kf, nvf, sA, dpA, lane);
             load_in(ntiles > 1 ? 1 : 0, 0, dpB);
+            // one step; next_m / next_v: stages of the tiles whose matrix / vector half comes in the step after
+            auto step = [&](f32x16 &s_nxt, f32x16 &dp_nxt, f32x16 &s_cur, f32x16 &dp_cur, int next_m, int next_v,
+                            int buf) {
+                score_step<D, 0, TB>(smem, at_stage(next_m), stats_s[next_m], stats_s[next_v], in, kf, nvf, s_nxt,
+                                     dp_nxt, s_cur, dp_cur, pds + (buf << 14), c, lane);
+                wait_lgkm<kScoreTail>();    // P / dS are in LDS before the next barrier publishes them
+            };
             int st = 0, t = 0;      // st = stage of tile t
             for (; t + 2 < ntiles; t += 2) {
                 const int st1 = next_stage(st), st2 = next_stage(st1), st3 = next_stage(st2);
                 step_barrier();                                       // step t: tile t+2 has landed
-                score_step<D>(in, kf, nvf, sB, dpB, sA, dpA, pds, c);
-                load_in(st2, st1, dpA);
+                step(sB, dpB, sA, dpA, st2, st1, 0);
                 step_barrier();                                       // step t + 1
-                score_step<D>(in, kf, nvf, sA, dpA, sB, dpB, pds + (1 << 14), c);
-                load_in(t + 3 < ntiles ? st3 : st2, st2, dpB);
+                step(sA, dpA, sB, dpB, t + 3 < ntiles ? st3 : st2, st2, 1);
                 st = st2;
             }
             if (t + 1 < ntiles) {                                     // two tiles left
                 const int st1 = next_stage(st);
                 step_barrier();
-                score_step<D>(in, kf, nvf, sB, dpB, sA, dpA, pds, c);
+                step(sB, dpB, sA, dpA, st1, st1, 0);                  // (the refills are not used)
                 wait_lgkm0();
                 step_barrier();
                 score_valu(stats_s[st1], sB, dpB, pds + (1 << 14), c, lane);
@@ -1105,7 +1143,8 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
                 }
                 f = tload(stn);
                 st = stn;
-                wait_lgkm0();
+                __builtin_amdgcn_sched_barrier(0);
+                wait_lgkm<8>();      // the P / dS reads are over (the 8 transposed tile reads behind them need not be)
             }
         } else {
             // one step behind, reading as it goes (partly filled or tail tiles)

@@ -197,6 +197,12 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 }
 // s_waitcnt that only waits for the wave's LDS (and scalar-memory) operations
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+// ... until at most N of them are outstanding. LDS operations complete in order, so this means: every LDS
+// operation older than the N youngest is done (outstanding scalar loads only make the wait longer).
+template <int N> __device__ __forceinline__ void wait_lgkm() {
+    static_assert(N >= 0 && N < 16, "lgkmcnt range");
+    __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));
+}
 
 // Asynchronous global -> LDS copies (global_load_lds): every lane moves BYTES
 // bytes from its own global address to LDS address  base + lane * BYTES, where
