@@ -23,9 +23,9 @@ from tests.test_gpu_parity import check_close, check_sel
 pytestmark = pytest.mark.gpu
 
 
-def _run(workload, window, head, n_sample, with_text_chunk, seed=1234):
+def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=None):
     cfg = mi.CONFIGS[workload]
-    lay = mi.config_layout(workload, window=window)
+    lay = mi.config_layout(workload, window=window, chunk=chunk)
     B, H, d, topk, N = cfg["B"], cfg["H"], cfg["d"], cfg["topk"], lay.N
     q, k, v, d_o = (t.to(torch.bfloat16).contiguous() for t in mi.qkv_do(B, H, N, d, seed, "cuda"))
     meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
@@ -104,3 +104,13 @@ def test_eight_shot_config_frame_window():
 def test_eight_shot_config_shot_window():
     """Config 4 with the whole shot as the forced local window (the multi-shot reading)."""
     _run("eight", "shot", head=2, n_sample=256, with_text_chunk=False)
+
+
+def test_sweep_config_chunk_130():
+    """BASELINE config 5 (32 shots, N = 457,472) at chunk 130: 3,488 chunks, 2-key tail tiles, k=8."""
+    _run("sweep", "frame", head=7, n_sample=192, with_text_chunk=False, chunk=130)
+
+
+def test_sweep_config_chunk_520():
+    """Config 5 at chunk 520: chunks longer than the chunk-resident routed forward takes (tiled routed path), 8-key tails."""
+    _run("sweep", "frame", head=11, n_sample=192, with_text_chunk=False, chunk=520)
