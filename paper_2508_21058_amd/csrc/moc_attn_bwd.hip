@@ -1133,13 +1133,13 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_pipe_kernel(KvArgs a) {
             for (int t = 2; t <= ntiles + 1; ++t) {
                 step_wait(t);
                 const int stn = t - 1 < ntiles ? next_stage(st) : st;     // past the end: any resident tile, unused
+                step_issue(t);       // first: measured best (better than between or behind the matrix instructions)
 #pragma unroll
                 for (int j = 0; j < KPW; ++j) {
                     gmfma(f, P[j], j);
                     __builtin_amdgcn_sched_barrier(0);
                     pload(t - 1, j, P[j]);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (j == KPW / 2 - 1) step_issue(t);
                 }
                 f = tload(stn);
                 st = stn;
