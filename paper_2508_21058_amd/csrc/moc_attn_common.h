@@ -198,27 +198,28 @@ template <int D, int ROWS> struct TileLoader<D, bf16_t, ROWS> {
     __device__ __forceinline__ int slot(int p) const { return wave + NW * p; }
     __device__ __forceinline__ explicit TileLoader(int tid)
         : wave(__builtin_amdgcn_readfirstlane(tid >> 6)), rlo((tid & 63) / (D / 8)), cgp((tid & 63) % (D / 8)) {}
-    static __device__ __forceinline__ void dma(const bf16_t *g, bf16_t *lds) { async_copy16(g, lds); }
     // arbitrary (gathered) rows: rowfn(r) is the global row of tile row r
     template <typename F> __device__ __forceinline__ void issue(const bf16_t *base, F rowfn, bf16_t *lds) const {
+        const uint32_t at = lds_address(lds);      // one pointer conversion per tile, not one per copy
 #pragma unroll
         for (int p = 0; p < P; ++p) {
             const int n = slot(p);
             const int row = n * RPI + rlo;
             const int cg = cgp ^ SwTile<D>::sw(row);
-            dma(base + (size_t)rowfn(row) * D + cg * 8, lds + n * 512);
+            async_copy16_at(base + (size_t)rowfn(row) * D + cg * 8, at + n * 1024);
         }
     }
     // contiguous rows [0, valid) of a tile whose first row is at `tile` (a
     // wave-uniform pointer): scalar base + one 32-bit lane offset per load
     __device__ __forceinline__ void issue_rows(const bf16_t *tile, int valid, bf16_t *lds) const {
+        const uint32_t at = lds_address(lds);
 #pragma unroll
         for (int p = 0; p < P; ++p) {
             const int n = slot(p);
             const int row = n * RPI + rlo;
             const int cg = cgp ^ SwTile<D>::sw(row);
             const uint32_t off = (uint32_t)(min(row, valid - 1) * D + cg * 8) * 2u;
-            async_copy16(tile, off, lds + n * 512);
+            async_copy16_at(tile, off, at + n * 1024);
         }
     }
     // the tile is complete once this wave's copies have landed (and the workgroup has met at a barrier)
