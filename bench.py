@@ -222,6 +222,16 @@ def main():
             if line.startswith(key):
                 roof["traffic"] = {"hbm_GB_per_launch": float(line.split("=")[1]), "source": "profiles/" + os.path.basename(tfile)}
 
+    # what this GPU sustains on a plain streaming copy and on a bare MFMA loop (context for the fractions above)
+    pbuf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    c_ms, c_bytes = mb.probe("copy", pbuf, 20)
+    m_ms, m_flops = mb.probe("mfma", pbuf, 100000)
+    del pbuf
+    measured = {"hbm_copy_GBs": round(c_bytes / (c_ms * 1e-3) / 1e9, 1),
+                "bf16_mfma_TFLOPs": round(m_flops / (m_ms * 1e-3) / 1e12, 1)}
+    roof["frac_of_measured"] = round(roof["achieved"] / (measured["bf16_mfma_TFLOPs"] if roof["bound"] == "mfma"
+                                                         else measured["hbm_copy_GBs"]), 4)
+
     out = {
         "metric": "routed_attn_tflops_fwd_bwd", "value": round(total_flops / (ms_step * 1e-3) / 1e12, 2),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -237,7 +247,7 @@ def main():
         "stage_ms": {"route": round(float(stage[0]), 3), "attn_fwd": round(float(stage[1]), 3),
                      "attn_bwd": round(float(stage[2]), 3), "chunk_meta_once": round(meta_ms, 3)},
         "keys_per_query": round(pairs / (BH * N), 1), "sparsity": round(1 - pairs / (BH * float(N) * N), 4),
-        "kernels": kernels, "roofline": roof,
+        "kernels": kernels, "roofline": roof, "measured_peaks": measured,
     }
     if args.cpu_queries > 0:
         out["cpu_baseline"] = cpu_baseline(lay, cfg, q, k, v, d_o, topk, args.cpu_queries)

@@ -159,6 +159,24 @@ int moc_attn_bwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtyp
 int moc_prof_enable(int on);
 int moc_prof_read(int32_t index, char *name, size_t name_cap, int32_t *launches, float *total_ms);
 
+/*
+ * Machine probes (measurement aid, not part of the layer): the rate this GPU
+ * sustains on the two resources the layer's kernels are priced against.
+ *   MOC_PROBE_COPY  streams the first half of `buf` (device, 16-byte aligned,
+ *                   `bytes` long) into the second half, `iters` times;
+ *                   *units = bytes read + bytes written.
+ *   MOC_PROBE_MFMA  runs `iters` iterations of 16 independent
+ *                   v_mfma_f32_32x32x16_bf16 per wave, 8 waves on each of 256
+ *                   workgroups; `buf` (>= 512 KiB) receives one float per lane;
+ *                   *units = flops issued.
+ * The call launches on `stream` (a hipStream_t, NULL = default), waits for the
+ * work, and stores the elapsed milliseconds (HIP events around the timed
+ * launches, after one untimed pass) in *ms (host). Returns MOC_OK or a
+ * negative moc_status; nothing is allocated on the device.
+ */
+enum moc_probe_kind { MOC_PROBE_COPY = 0, MOC_PROBE_MFMA = 1 };
+int moc_probe(int32_t kind, void *buf, size_t bytes, int32_t iters, void *stream, float *ms, double *units);
+
 #ifdef __cplusplus
 }
 #endif

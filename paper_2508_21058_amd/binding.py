@@ -24,7 +24,7 @@ MOC_MAX_TOPK = 32
 
 SYMBOLS = ["moc_status_string", "moc_last_error", "moc_chunk_meta", "moc_meta_destroy", "moc_meta_copy_tables",
            "moc_route_workspace_bytes", "moc_route", "moc_attn_workspace_bytes", "moc_attn_fwd", "moc_attn_bwd",
-           "moc_prof_enable", "moc_prof_read"]
+           "moc_prof_enable", "moc_prof_read", "moc_probe"]
 
 
 class MocError(RuntimeError):
@@ -222,3 +222,13 @@ def prof_read():
         _check(lib().moc_prof_read(i, buf, 128, C.byref(cnt), C.byref(ms)), "moc_prof_read")
         out[buf.value.decode()] = (cnt.value, ms.value)
     return out
+
+
+def probe(kind: str, buf: torch.Tensor, iters: int):
+    """Machine probe: kind 'copy' streams the first half of `buf` into the second, 'mfma' runs
+    a loop of independent bf16 MFMA chains. -> (milliseconds, bytes moved or flops issued)."""
+    assert buf.is_cuda and buf.is_contiguous()
+    ms, units = C.c_float(), C.c_double()
+    _check(lib().moc_probe({"copy": 0, "mfma": 1}[kind], _ptr(buf), C.c_size_t(buf.numel() * buf.element_size()),
+                           int(iters), _stream(), C.byref(ms), C.byref(units)), "moc_probe")
+    return ms.value, units.value

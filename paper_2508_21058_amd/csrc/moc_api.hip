@@ -165,6 +165,27 @@ int moc_prof_read(int32_t index, char *name, size_t name_cap, int32_t *launches,
     return MOC_OK;
 }
 
+int moc_probe(int32_t kind, void *buf, size_t bytes, int32_t iters, void *stream, float *ms, double *units) {
+    if (!buf || !ms || !units) return fail(MOC_ERR_NULL, "moc_probe: NULL argument");
+    if (kind != MOC_PROBE_COPY && kind != MOC_PROBE_MFMA) return fail(MOC_ERR_SHAPE, "moc_probe: unknown kind");
+    if (iters <= 0) return fail(MOC_ERR_SHAPE, "moc_probe: iters must be positive");
+    if (misaligned(buf)) return fail(MOC_ERR_ALIGN, "moc_probe: buffer must be 16-byte aligned");
+    if (kind == MOC_PROBE_COPY && bytes < 32) return fail(MOC_ERR_WORKSPACE, "moc_probe: copy needs at least 32 bytes");
+    if (kind == MOC_PROBE_MFMA && bytes < (size_t)moc::kProbeMfmaGrid * 512 * sizeof(float))
+        return fail(MOC_ERR_WORKSPACE, "moc_probe: mfma needs a 512 KiB buffer");
+    hipEvent_t e0, e1;
+    hipError_t e = hipEventCreate(&e0);
+    if (e != hipSuccess) return hip_fail(e, "moc_probe");
+    e = hipEventCreate(&e1);
+    if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e, "moc_probe"); }
+    e = moc::launch_probe(kind, buf, bytes, iters, (hipStream_t)stream, e0, e1, units);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return e == hipSuccess ? MOC_OK : hip_fail(e, "moc_probe");
+}
+
 int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot, const int32_t *window,
                    const int32_t *spans, int32_t T, void *stream, moc_meta **out) {
     using namespace moc;

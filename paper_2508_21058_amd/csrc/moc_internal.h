@@ -69,6 +69,11 @@ struct ProfScope {
 };
 #define MOC_PROF(name, st) ::moc::ProfScope moc_prof_scope_(name, st)
 
+// Machine probes (streaming copy, MFMA loop); see moc_probe.
+constexpr int kProbeMfmaGrid = 256;
+hipError_t launch_probe(int kind, void *buf, size_t bytes, int iters, hipStream_t st, hipEvent_t e0, hipEvent_t e1,
+                        double *units);
+
 // Layout of the attention workspace (byte offsets); shared by fwd and bwd.
 struct AttnWs {
     size_t cnt, list_off, tile_off, cursor, qlist, plse, po, delta, stats2, gstats2, tpart_k, tpart_v, total;

@@ -1,0 +1,68 @@
+// Machine probes (measurement aids, not part of the layer): what one GPU
+// sustains on a plain streaming copy and on a loop of independent bf16 MFMA
+// chains. The bench reports the layer's kernels against these measured rates
+// beside the published peaks.
+#include "moc_internal.h"
+#include "moc_device.h"
+
+namespace moc {
+
+// Each lane moves 16 bytes per iteration; the grid strides over the buffer.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
+                                                         size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// Eight waves per workgroup (two per SIMD), each running four independent
+// accumulator chains of v_mfma_f32_32x32x16_bf16: 16 MFMAs per iteration per wave.
+__global__ __launch_bounds__(512) void probe_mfma_kernel(float *__restrict__ out, int iters) {
+    bf16x8 a, b;
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(1.f + 0.125f * ((threadIdx.x + i) & 3));
+        b[i] = (__bf16)(0.0078125f * (1 + ((threadIdx.x * 3 + i) & 7)));
+    }
+    f32x16 c0 = zero16(), c1 = zero16(), c2 = zero16(), c3 = zero16();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            c0 = mfma32(a, b, c0);
+            c1 = mfma32(b, a, c1);
+            c2 = mfma32(a, a, c2);
+            c3 = mfma32(b, b, c3);
+        }
+    }
+    float s = 0.f;
+    for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+    out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
+// Runs one probe on `st` bracketed by the two events; `units` receives the bytes
+// moved (copy: read + written) or the flops issued (mfma) inside the bracket.
+hipError_t launch_probe(int kind, void *buf, size_t bytes, int iters, hipStream_t st, hipEvent_t e0, hipEvent_t e1,
+                        double *units) {
+    if (kind == MOC_PROBE_COPY) {
+        const size_t n16 = bytes / 32;                  // 16-byte words in each half
+        const u32x4 *src = (const u32x4 *)buf;
+        u32x4 *dst = (u32x4 *)buf + n16;
+        const int grid = 256 * 16;
+        probe_copy_kernel<<<grid, 256, 0, st>>>(src, dst, n16);          // untimed first pass
+        (void)hipEventRecord(e0, st);
+        for (int i = 0; i < iters; ++i) probe_copy_kernel<<<grid, 256, 0, st>>>(src, dst, n16);
+        (void)hipEventRecord(e1, st);
+        *units = 2.0 * 16.0 * (double)n16 * iters;
+    } else {
+        const int grid = kProbeMfmaGrid;                // one workgroup per compute unit
+        probe_mfma_kernel<<<grid, 512, 0, st>>>((float *)buf, 16);       // untimed first pass
+        (void)hipEventRecord(e0, st);
+        probe_mfma_kernel<<<grid, 512, 0, st>>>((float *)buf, iters);
+        (void)hipEventRecord(e1, st);
+        // 16 MFMAs per iteration per wave, 2*32*32*16 flops each, 8 waves per workgroup
+        *units = 16.0 * 32768.0 * 8.0 * grid * (double)iters;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace moc

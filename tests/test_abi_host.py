@@ -76,3 +76,15 @@ def test_null_and_shape_errors():
     assert lib.moc_attn_workspace_bytes(None, 1, 1, 128, 4, 0, 0, C.byref(n)) == -1
     assert lib.moc_route(None, 1, 1, 128, 0, None, None, 4, 1, None, None, None, 0, None) == -1
     assert lib.moc_attn_fwd(None, 1, 1, 128, 0, None, None, None, None, 4, 0.1, None, None, None, 0, None) == -1
+
+
+def test_probe_rejects_bad_arguments_before_any_launch():
+    lib = mb.lib()
+    ms, units = C.c_float(), C.c_double()
+    assert lib.moc_probe(0, None, C.c_size_t(64), 1, None, C.byref(ms), C.byref(units)) == -1
+    fake = C.c_void_p(0x1000)                       # never dereferenced: every call below is rejected on the host
+    assert lib.moc_probe(7, fake, C.c_size_t(64), 1, None, C.byref(ms), C.byref(units)) == -2
+    assert lib.moc_probe(0, fake, C.c_size_t(64), 0, None, C.byref(ms), C.byref(units)) == -2
+    assert lib.moc_probe(0, C.c_void_p(0x1004), C.c_size_t(64), 1, None, C.byref(ms), C.byref(units)) == -8
+    assert lib.moc_probe(0, fake, C.c_size_t(16), 1, None, C.byref(ms), C.byref(units)) == -7
+    assert lib.moc_probe(1, fake, C.c_size_t(4096), 1, None, C.byref(ms), C.byref(units)) == -7

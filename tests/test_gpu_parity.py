@@ -197,3 +197,16 @@ def test_end_to_end_route_then_attend_matches_oracle_sets():
     assert same.mean() > 0.999
     check_close("o", o.float().cpu().numpy()[same], ref["o"][same])
     meta.close()
+
+
+@pytest.mark.gpu
+def test_probes_copy_exactly_and_report_plausible_rates():
+    """The streaming-copy probe really copies; both probes report rates below the published peaks."""
+    buf = torch.randint(0, 255, (1 << 26,), dtype=torch.uint8, device="cuda")
+    first = buf[: 1 << 25].clone()
+    ms, nbytes = mb.probe("copy", buf, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(buf[1 << 25:], first) and torch.equal(buf[: 1 << 25], first)
+    assert nbytes == 3 * 2.0 * (1 << 25) and 0 < nbytes / (ms * 1e-3) < 8.0e12
+    ms, flops = mb.probe("mfma", buf, 2000)
+    assert 0 < flops / (ms * 1e-3) < 2.6e15
