@@ -31,7 +31,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
-def layout_counts(lay, sel, chunk_of_t, topk):
+def layout_counts(lay, sel, chunk_of_t, topk, causal=True):
     """Attended (query, key) pairs per head-sum, split into forced and routed, and
     the number of routing candidates - all from the layout and the selection."""
     import torch
@@ -58,11 +58,14 @@ def layout_counts(lay, sel, chunk_of_t, topk):
         first_of_win[w] = np.nonzero(winv == w)[0][0]
     own_before = np.array([np.sum((~is_text)[first_of_win[winv[c]]:c]) for c in range(C)])
     elig_per_chunk = nontext_before - own_before
+    if not causal:           # every non-text chunk outside the own window
+        win_nt_chunks = np.bincount(winv, weights=(~is_text).astype(np.float64), minlength=len(wids))
+        elig_per_chunk = (~is_text).sum() - win_nt_chunks[winv]
     eligible = float((elig_per_chunk * lens).sum())               # per head
     return forced_pairs, routed_pairs, eligible
 
 
-def cpu_baseline(lay, cfg, q, k, v, d_o, topk, budget_queries):
+def cpu_baseline(lay, cfg, q, k, v, d_o, topk, budget_queries, causal=True):
     """Oracle on one head: the queries that attend eight sampled video chunks plus
     random queries up to `budget_queries`: forward + dQ for those queries, dK/dV
     for the sampled chunks. Algorithmic FLOPs as for the GPU path."""
@@ -74,7 +77,7 @@ def cpu_baseline(lay, cfg, q, k, v, d_o, topk, budget_queries):
     rng = np.random.default_rng(0)
     t0 = time.perf_counter()
     kbar = mo.pool(L, kn)
-    sel_all, _ = mo.route(L, qn, kbar, topk, True)
+    sel_all, _ = mo.route(L, qn, kbar, topk, causal)
     t_route = time.perf_counter() - t0
     video = np.nonzero(L.kind == 0)[0]
     chunks = np.sort(rng.choice(video[len(video) // 4:], size=min(8, len(video)), replace=False)).astype(np.int32)
@@ -109,7 +112,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="eight", choices=["eight", "single", "tiny", "sweep"])
+    ap.add_argument("--workload", default="eight", choices=["eight", "single", "tiny", "sweep", "short", "paper"])
     ap.add_argument("--window", default=None, choices=[None, "frame", "shot", "chunk"])
     ap.add_argument("--chunk", type=int, default=None)
     ap.add_argument("--topk", type=int, default=None)
@@ -135,6 +138,7 @@ def main():
         cfg["topk"] = args.topk
     lay = mi.config_layout(args.workload, window=args.window, chunk=args.chunk)
     B, H, d, topk, N = cfg["B"], cfg["H"], cfg["d"], cfg["topk"], lay.N
+    causal = bool(cfg.get("causal", True))
     tdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
     q, k, v, d_o = (t.to(tdt).contiguous() for t in mi.qkv_do(B, H, N, d, args.seed, "cuda"))
     if args.inputs == "S2":
@@ -155,7 +159,7 @@ def main():
 
     def step(ev=None):
         if ev: ev[0].record()
-        pooled, sel = mb.route(meta, q, k, topk, True)
+        pooled, sel = mb.route(meta, q, k, topk, causal)
         if ev: ev[1].record()
         mb.attn_fwd(meta, q, k, v, sel, None, ws, (o, lse))
         if ev: ev[2].record()
@@ -177,9 +181,10 @@ def main():
     kern = mb.prof_read()
     mb.prof_enable(False)
     ms_step = wall * 1e3 / args.steps
-    stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in evs]).mean(0)
+    stage_all = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in evs])
+    stage = stage_all.mean(0)
 
-    forced_pairs, routed_pairs, eligible = layout_counts(lay, sel, None, topk)
+    forced_pairs, routed_pairs, eligible = layout_counts(lay, sel, None, topk, causal)
     BH = B * H
     pairs_f, pairs_r = forced_pairs * BH, routed_pairs
     pairs = pairs_f + pairs_r
@@ -232,13 +237,31 @@ def main():
     roof["frac_of_measured"] = round(roof["achieved"] / (measured["bf16_mfma_TFLOPs"] if roof["bound"] == "mfma"
                                                          else measured["hbm_copy_GBs"]), 4)
 
+    # routing: bytes as asked, and the score contraction's rate on the unit it runs on (three bf16 MFMA planes
+    # per candidate score); the top-k pass is bound by that work, not by HBM, once a query has hundreds of candidates
+    routing = {}
+    if "pool" in kernels:
+        routing["pool_GBs"] = kernels["pool"]["gbs"]
+        routing["pool_frac_of_hbm_peak"] = round(kernels["pool"]["gbs"] / PEAK_HBM_GBS, 4)
+    if "route_topk" in kernels:
+        r_ms = kernels["route_topk"]["ms"]
+        routing["score_topk_GBs"] = kernels["route_topk"]["gbs"]
+        routing["score_topk_frac_of_hbm_peak"] = round(kernels["route_topk"]["gbs"] / PEAK_HBM_GBS, 4)
+        routing["score_TFLOPs_algorithmic"] = round(2.0 * d * eligible * BH / (r_ms * 1e-3) / 1e12, 2)
+        routing["candidates_per_query"] = round(eligible / N, 1)
+        routing["bound"] = "mfma+selection" if eligible / N >= 300 else "hbm"
+    # the same step priced as a dense causal attention of the same length (2 N^2 d per head forward, x3.5)
+    dense_flops = 3.5 * 2.0 * float(N) * N * d * BH
+    dense = {"flops": dense_flops, "equivalent_TFLOPs": round(dense_flops / (ms_step * 1e-3) / 1e12, 1),
+             "flop_ratio_dense_over_routed": round(dense_flops / total_flops, 2)}
+
     out = {
         "metric": "routed_attn_tflops_fwd_bwd", "value": round(total_flops / (ms_step * 1e-3) / 1e12, 2),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if tdt == torch.bfloat16 else "f32(bf16 mfma)", "data": "synthetic",
         "config": {"workload": f"{args.workload} ({lay.name}): B={B} H={H} N={N} d={d} C={lay.C} "
-                               f"chunk={lay.meta.get('chunk')} window={lay.meta.get('window')} topk={topk} causal",
+                               f"chunk={lay.meta.get('chunk')} window={lay.meta.get('window')} topk={topk} {'causal' if causal else 'non-causal'}",
                    "inputs": ("S1 iid N(0,1) rounded to bf16, seeded" if args.inputs == "S1" else
                               "S2 chunk-coherent q and k (rho = 0.9, planted earlier target chunk), v and dO iid, seeded"),
                    "pass": "route + attn fwd + attn bwd"},
@@ -246,11 +269,14 @@ def main():
         "attn_only_tflops": round(total_flops / ((stage[1] + stage[2]) * 1e-3) / 1e12, 2),
         "stage_ms": {"route": round(float(stage[0]), 3), "attn_fwd": round(float(stage[1]), 3),
                      "attn_bwd": round(float(stage[2]), 3), "chunk_meta_once": round(meta_ms, 3)},
+        "stage_ms_median": [round(float(x), 3) for x in np.median(stage_all, 0)],
+        "stage_ms_min": [round(float(x), 3) for x in stage_all.min(0)],
+        "routing": routing, "dense_equivalent": dense,
         "keys_per_query": round(pairs / (BH * N), 1), "sparsity": round(1 - pairs / (BH * float(N) * N), 4),
         "kernels": kernels, "roofline": roof, "measured_peaks": measured,
     }
     if args.cpu_queries > 0:
-        out["cpu_baseline"] = cpu_baseline(lay, cfg, q, k, v, d_o, topk, args.cpu_queries)
+        out["cpu_baseline"] = cpu_baseline(lay, cfg, q, k, v, d_o, topk, args.cpu_queries, causal)
     print(json.dumps(out))
 
 

@@ -108,6 +108,39 @@ def multishot_layout(n_shots: int, text_len: int, frames: int, frame_tokens: int
                    frame_tokens=frame_tokens, chunk=chunk, window=window)
 
 
+def stream_layout(n_shots: int, text_len: int, video_tokens: int, chunk: int, window: str = "shot",
+                  name: str = "") -> Layout:
+    """Per shot [caption span | video_tokens], the video cut every ``chunk`` tokens with a ragged
+    last chunk, never across a shot boundary (App. "Training Details": fixed chunk sizes over the
+    flattened stream). window: "chunk" (own chunk) or "shot" (the whole shot, caption included)."""
+    if window not in ("chunk", "shot"):
+        raise ValueError(window)
+    offs, shot, win, spans = [0], [], [], []
+    wid = 0
+    for s in range(n_shots):
+        if text_len > 0:
+            start = offs[-1]
+            offs.append(start + text_len)
+            spans.append((start, start + text_len))
+            shot.append(s)
+            win.append(wid)
+            if window == "chunk":
+                wid += 1
+        left = video_tokens
+        while left > 0:
+            m = min(chunk, left)
+            offs.append(offs[-1] + m)
+            shot.append(s)
+            win.append(wid)
+            if window == "chunk":
+                wid += 1
+            left -= m
+        if window == "shot":
+            wid += 1
+    return _finish(name or f"{n_shots}shot_stream_c{chunk}_{window}", offs, shot, win, spans,
+                   n_shots=n_shots, text_len=text_len, video_tokens=video_tokens, chunk=chunk, window=window)
+
+
 def random_layout(seed: int, n_chunks: int = 12, max_len: int = 40, n_shots: int = 2,
                   text_prob: float = 0.2, window: str = "mixed") -> Layout:
     """Small irregular layout for brute-force tests: chunk lengths 1..max_len,
@@ -162,6 +195,10 @@ def config_layout(cfg: str, window: Optional[str] = None, chunk: Optional[int] =
         return multishot_layout(8, 256, 9, 1560, chunk or 260, window or "frame", "eight")
     if cfg == "sweep":       # 32 x (256 text + 9 frames x 1560), chunk in {130,260,520}
         return multishot_layout(32, 256, 9, 1560, chunk or 260, window or "frame", "sweep")
+    if cfg == "short":       # single-shot training set-up: 256 text + 6,000 video tokens, chunk 256, own-chunk window
+        return stream_layout(1, 256, 6000, chunk or 256, window or "chunk", "short")
+    if cfg == "paper":       # multi-shot training set-up: 8 x (256 text + 14,040 video), chunk 10240 ... 1280, shot window
+        return stream_layout(8, 256, 14040, chunk or 1280, window or "shot", "paper")
     raise ValueError(cfg)
 
 
@@ -171,6 +208,9 @@ CONFIGS = {
     "single": dict(B=1, H=24, d=128, dtype="bf16", topk=5),
     "eight":  dict(B=1, H=24, d=128, dtype="bf16", topk=8),
     "sweep":  dict(B=1, H=24, d=128, dtype="bf16", topk=8),
+    # the two training set-ups of App. "Training Details" (no causal mask in the single-shot one)
+    "short":  dict(B=1, H=24, d=128, dtype="bf16", topk=3, causal=False),
+    "paper":  dict(B=1, H=24, d=128, dtype="bf16", topk=5),
 }
 
 

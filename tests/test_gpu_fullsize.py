@@ -23,13 +23,14 @@ from tests.test_gpu_parity import check_close, check_sel
 pytestmark = pytest.mark.gpu
 
 
-def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=None):
-    cfg = mi.CONFIGS[workload]
-    lay = mi.config_layout(workload, window=window, chunk=chunk)
+def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=None, lay=None, cfg=None, n_chunks=2):
+    cfg = cfg or mi.CONFIGS[workload]
+    lay = lay or mi.config_layout(workload, window=window, chunk=chunk)
     B, H, d, topk, N = cfg["B"], cfg["H"], cfg["d"], cfg["topk"], lay.N
+    causal = bool(cfg.get("causal", True))
     q, k, v, d_o = (t.to(torch.bfloat16).contiguous() for t in mi.qkv_do(B, H, N, d, seed, "cuda"))
     meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
-    pooled, sel = mb.route(meta, q, k, topk, True)
+    pooled, sel = mb.route(meta, q, k, topk, causal)
     torch.cuda.synchronize()
 
     L = mo.OracleLayout.from_layout(lay)
@@ -42,12 +43,12 @@ def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=Non
     assert err <= 1e-5, f"pooled keys rel err {err:.3e}"
 
     # stage c: selections of the whole head
-    sel_ref, _ = mo.route(L, qn, kbar, topk, True)
+    sel_ref, _ = mo.route(L, qn, kbar, topk, causal)
     sel_gpu = sel[0, head].cpu().numpy()
     bad = np.nonzero((np.sort(sel_gpu, -1) != np.sort(sel_ref[0, 0], -1)).any(-1))[0].astype(np.int32)
     if len(bad):
         assert len(bad) <= max(2, N // 2000), f"{len(bad)} rows differ"
-        _, sc, _ = mo.route(L, qn, kbar, topk, True, bad, want_scores=True)
+        _, sc, _ = mo.route(L, qn, kbar, topk, causal, bad, want_scores=True)
         check_sel(sel_gpu[bad], sel_ref[0, 0][bad], sc[0, 0], topk)
     # order inside rows (best first) where the sets agree
     same = np.setdiff1d(np.arange(N), bad)
@@ -62,7 +63,7 @@ def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=Non
 
     rng = np.random.default_rng(5)
     video = np.nonzero(L.kind == 0)[0]
-    chunks = list(rng.choice(video[len(video) // 3:], size=2, replace=False))
+    chunks = list(rng.choice(video[len(video) // 3:], size=n_chunks, replace=False))
     if with_text_chunk:
         chunks.append(int(np.nonzero(L.kind == 1)[0][0]))
     chunks = np.array(sorted(chunks), dtype=np.int32)
@@ -114,3 +115,27 @@ def test_sweep_config_chunk_130():
 def test_sweep_config_chunk_520():
     """Config 5 at chunk 520: chunks longer than the chunk-resident routed forward takes (tiled routed path), 8-key tails."""
     _run("sweep", "frame", head=11, n_sample=192, with_text_chunk=False, chunk=520)
+
+
+def test_single_shot_training_setup_non_causal():
+    """App. "Training Details", single-shot model: ~6.3k tokens, chunk 256 (ragged last chunk of 112),
+    own-chunk window, k=3, no causal mask: candidates on both sides of the query."""
+    _run("short", None, head=9, n_sample=512, with_text_chunk=True, n_chunks=3)
+
+
+def test_multi_shot_training_setup_chunk_1280():
+    """App. "Training Details", multi-shot model at its final chunk size: 8 x (256 text + 14,040 video),
+    chunks of 1280 with a ragged 1240 tail per shot, whole-shot window, k=5."""
+    _run("paper", None, head=3, n_sample=128, with_text_chunk=False, chunk=1280)
+
+
+def test_multi_shot_training_setup_chunk_2560():
+    _run("paper", None, head=20, n_sample=128, with_text_chunk=False, chunk=2560, n_chunks=1)
+
+
+def test_chunks_of_10240_tokens():
+    """The largest chunk size of the multi-shot schedule on a two-shot stream: fewer candidates (2)
+    than k (5), every routed list covers a whole shot, 80 key tiles share one chunk's query list."""
+    lay = mi.stream_layout(2, 64, 12000, 10240, "shot")
+    cfg = dict(B=1, H=2, d=128, dtype="bf16", topk=5)
+    _run(None, None, head=1, n_sample=64, with_text_chunk=False, lay=lay, cfg=cfg, n_chunks=1)

@@ -294,3 +294,35 @@ def test_sparsity_of_eight_shot_shot_window_matches_paper():
         pairs += (text + fr * ft) * (S * text + fr * ft + min(k, earlier) * ch)
     sparsity = 1 - pairs / N ** 2
     assert 0.83 < sparsity < 0.87
+
+
+@pytest.mark.parametrize("chunk", [10240, 5120, 2560, 1280])
+def test_stream_layout_cuts_every_shot_on_its_own(chunk):
+    """Fixed-size chunking of the flattened stream with shot-aligned boundaries (App. "Training
+    Details"): no chunk crosses a shot or a caption boundary, only a shot's last chunk is short,
+    and with the shot window the forced keys of a video query are its whole shot plus every caption."""
+    lay = mi.config_layout("paper", chunk=chunk)
+    lens = np.diff(lay.offsets)
+    per_shot = 256 + 14040
+    assert lay.N == 8 * per_shot and (lens > 0).all()
+    for j in range(lay.C):
+        s0, s1 = divmod(int(lay.offsets[j]), per_shot)[0], divmod(int(lay.offsets[j + 1]) - 1, per_shot)[0]
+        assert s0 == s1 == lay.shot[j] == lay.window[j]
+    video = np.ones(lay.C, bool)
+    video[[np.searchsorted(lay.offsets, s) for s, _ in lay.text_spans]] = False
+    tail = np.nonzero(video & (lens != chunk))[0]
+    assert len(tail) == (8 if 14040 % chunk else 0) and (lens[tail] == 14040 % chunk).all()
+    L = mo.OracleLayout.from_layout(lay)
+    d = 4
+    qidx = np.array([300, per_shot + 5000, 7 * per_shot + 14000], np.int32)
+    q, k = _rand((1, 1, lay.N, d), 1), _rand((1, 1, lay.N, d), 2)
+    sel, _ = mo.route(L, q, mo.pool(L, k), 5, True, qidx)
+    per_video_chunks = -(-14040 // chunk)
+    for r, i in enumerate(qidx):
+        s = int(i) // per_shot
+        got = sel[0, 0, r][sel[0, 0, r] >= 0]
+        assert len(got) == min(5, s * per_video_chunks)            # candidates: video chunks of earlier shots
+        assert (lay.shot[got] < s).all() and video[got].all()
+    _, _, n_pairs = mo.attn_fwd(L, q, k, k, sel, None, qidx)
+    want = sum(8 * 256 + 14040 + int(lens[sel[0, 0, r][sel[0, 0, r] >= 0]].sum()) for r in range(3))
+    assert n_pairs == want
