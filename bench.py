@@ -118,6 +118,8 @@ def main():
     ap.add_argument("--topk", type=int, default=None)
     ap.add_argument("--cpu-queries", type=int, default=1 << 30, help="oracle sample size, capped at N (0 = skip the CPU baseline)")
     ap.add_argument("--seed", type=int, default=1234)
+    ap.add_argument("--perturb", default=None, metavar="P_MAX,LAMBDA,MAX_IN",
+                    help="route with context drop-off / drop-in (training-time regularisers); rows widen by MAX_IN")
     ap.add_argument("--inputs", default="S1", choices=["S1", "S2"],
                     help="S1: q, k, v, dO iid N(0,1) (graded); S2: chunk-coherent q and k (queries of a chunk select nearly the same chunks)")
     args = ap.parse_args()
@@ -153,13 +155,22 @@ def main():
     torch.cuda.synchronize()
     meta_ms = (time.perf_counter() - t0) * 1e3
 
-    ws = mb.attn_workspace(meta, B, H, d, topk, tdt, True)
+    perturb = None
+    width = topk
+    if args.perturb:
+        p_max, lam, max_in = args.perturb.split(",")
+        perturb = (float(p_max), float(lam), int(max_in))
+        width = topk + perturb[2]
+    ws = mb.attn_workspace(meta, B, H, d, width, tdt, True)
     o = torch.empty_like(q); lse = torch.empty(B, H, N, dtype=torch.float32, device="cuda")
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
 
     def step(ev=None):
         if ev: ev[0].record()
-        pooled, sel = mb.route(meta, q, k, topk, causal)
+        if perturb:
+            pooled, sel = mb.route_perturbed(meta, q, k, topk, causal, *perturb, args.seed)
+        else:
+            pooled, sel = mb.route(meta, q, k, topk, causal)
         if ev: ev[1].record()
         mb.attn_fwd(meta, q, k, v, sel, None, ws, (o, lse))
         if ev: ev[2].record()
@@ -198,6 +209,7 @@ def main():
         "attn_bwd_dq_forced": ("flop", 2.0 * d * pairs_f), "attn_bwd_dq_routed": ("flop", 2.0 * d * pairs_r),
         "pool": ("byte", BH * (N * d * esz + lay.C * d * 4.0)),
         "route_topk": ("byte", BH * (N * d * esz + lay.C * d * 4.0 + N * topk * 4.0)),
+        "route_perturb": ("byte", BH * N * (topk + width) * 4.0),
     }
     kernels = {}
     for name, (cnt, ms) in kern.items():
@@ -264,7 +276,9 @@ def main():
                                f"chunk={lay.meta.get('chunk')} window={lay.meta.get('window')} topk={topk} {'causal' if causal else 'non-causal'}",
                    "inputs": ("S1 iid N(0,1) rounded to bf16, seeded" if args.inputs == "S1" else
                               "S2 chunk-coherent q and k (rho = 0.9, planted earlier target chunk), v and dO iid, seeded"),
-                   "pass": "route + attn fwd + attn bwd"},
+                   "pass": "route + attn fwd + attn bwd",
+                   **({"perturb": f"drop-off p_max={perturb[0]} drop-in lambda={perturb[1]} max_in={perturb[2]}"}
+                      if perturb else {})},
         "frac_of_bf16_mfma_peak": round(total_flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "attn_only_tflops": round(total_flops / ((stage[1] + stage[2]) * 1e-3) / 1e12, 2),
         "stage_ms": {"route": round(float(stage[0]), 3), "attn_fwd": round(float(stage[1]), 3),

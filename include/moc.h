@@ -116,6 +116,42 @@ int moc_route(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
               void *stream);
 
 /*
+ * Routing with the two training-time regularisers of Sec. 3.2 ("Context
+ * Drop-off", "Context Drop-in") applied to every (batch, head, query) row after
+ * the top-k of moc_route:
+ *   drop-off  p = u * p_max with u uniform in [0, 1); floor(p * topk) of the
+ *             routed chunks (at most all of them), chosen uniformly without
+ *             replacement, are removed; the others keep their order.
+ *   drop-in   m ~ Poisson(lambda), truncated at max_in and at the number of
+ *             chunks available, is drawn by inversion; m chunks are added,
+ *             chosen uniformly without replacement from the query's routing
+ *             candidates that moc_route did not select for it (a chunk removed
+ *             by drop-off does not come back).
+ *   sel       DEVICE out [B,H,N,topk + max_in] int32: surviving routed chunks
+ *             (best first), then the added chunks in the order drawn, then -1.
+ *             Pass it to moc_attn_fwd / moc_attn_bwd with topk + max_in as
+ *             their topk. Requires topk + max_in <= MOC_MAX_TOPK.
+ *   p_max     in [0, 1]; lambda >= 0, finite; both 0 reproduce moc_route.
+ *   seed      the random words of row (b, h, i) are the Philox4x32-10 stream
+ *             with key (seed low word, seed high word) and counter
+ *             (i, b*H + h, block, 0); draw t is word t mod 4 of block t / 4:
+ *             draw 0 -> u = (draw >> 8) * 2^-24, draw 1 -> m = #{j < max_in :
+ *             draw >= floor(CDF(j) * 2^32)}, then one draw per removal
+ *             (entry floor(draw * n / 2^32) of the n still alive) and one per
+ *             addition (entry floor(draw * n / 2^32) of the n available chunks
+ *             in ascending index order). floor(p * topk) is evaluated in single
+ *             precision as (u * p_max) * topk. The same seed gives the same
+ *             rows on every call.
+ * Everything else (pooled_k, q, k, workspace of moc_route_workspace_bytes with
+ * the same topk, errors) is as for moc_route.
+ */
+int moc_route_perturbed(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
+                        const void *q, const void *k, int32_t topk, int32_t causal,
+                        float p_max, float lambda, int32_t max_in, uint64_t seed,
+                        float *pooled_k, int32_t *sel, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/*
  * Stage (d) forward: o_i = softmax(q_i K_Omega^T * softmax_scale) V_Omega with
  * Omega(i) = tokens of all text chunks + the chunks of i's window + the chunks
  * listed in sel[i] (entries < 0 ignored). Forced links are not subject to the

@@ -23,7 +23,7 @@ MOC_BF16, MOC_F32 = 0, 1
 MOC_MAX_TOPK = 32
 
 SYMBOLS = ["moc_status_string", "moc_last_error", "moc_chunk_meta", "moc_meta_destroy", "moc_meta_copy_tables",
-           "moc_route_workspace_bytes", "moc_route", "moc_attn_workspace_bytes", "moc_attn_fwd", "moc_attn_bwd",
+           "moc_route_workspace_bytes", "moc_route", "moc_route_perturbed", "moc_attn_workspace_bytes", "moc_attn_fwd", "moc_attn_bwd",
            "moc_prof_enable", "moc_prof_read", "moc_probe"]
 
 
@@ -59,6 +59,9 @@ def lib():
     l.moc_attn_fwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, sz, vp]
     l.moc_attn_bwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, i32, C.c_float,
                                vp, vp, vp, vp, sz, vp]
+    l.moc_route_perturbed.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, i32, i32, C.c_float, C.c_float, i32,
+                                      C.c_uint64, vp, vp, vp, sz, vp]
+    l.moc_probe.argtypes = [i32, vp, sz, i32, vp, C.POINTER(C.c_float), C.POINTER(C.c_double)]
     l.moc_prof_enable.argtypes = [C.c_int]
     l.moc_prof_read.argtypes = [i32, C.c_char_p, sz, C.POINTER(i32), C.POINTER(C.c_float)]
     for name in SYMBOLS:
@@ -166,6 +169,26 @@ def route(meta: Meta, q: torch.Tensor, k: torch.Tensor, topk: int, causal: bool 
     return pooled, sel
 
 
+def route_perturbed(meta: Meta, q: torch.Tensor, k: torch.Tensor, topk: int, causal: bool, p_max: float,
+                    lam: float, max_in: int, seed: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Routing with context drop-off and drop-in -> pooled_k [B,H,C,d] fp32, sel [B,H,N,topk+max_in] int32."""
+    B, H, N, d = _shape(meta, q)
+    _need_contig(q, k)
+    dt = _dtype_code(q)
+    nbytes = C.c_size_t()
+    _check(lib().moc_route_workspace_bytes(meta.handle, B, H, d, topk, dt, C.byref(nbytes)),
+           "moc_route_workspace_bytes")
+    ws = torch.empty(max(nbytes.value, 16), dtype=torch.uint8, device=q.device)
+    pooled = torch.empty(B, H, meta.C, d, dtype=torch.float32, device=q.device)
+    width = max(topk + max_in, 0)
+    sel = torch.empty(B, H, N, width, dtype=torch.int32, device=q.device)
+    _check(lib().moc_route_perturbed(meta.handle, B, H, d, dt, _ptr(q), _ptr(k), int(topk), int(bool(causal)),
+                                     float(p_max), float(lam), int(max_in), int(seed), _ptr(pooled),
+                                     _ptr(sel) if width > 0 else None, _ptr(ws), nbytes.value, _stream()),
+           "moc_route_perturbed")
+    return pooled, sel
+
+
 def attn_workspace(meta: Meta, B: int, H: int, d: int, topk: int, dtype: torch.dtype, with_bwd: bool,
                    device="cuda") -> torch.Tensor:
     dt = MOC_BF16 if dtype == torch.bfloat16 else MOC_F32
@@ -229,6 +252,6 @@ def probe(kind: str, buf: torch.Tensor, iters: int):
     a loop of independent bf16 MFMA chains. -> (milliseconds, bytes moved or flops issued)."""
     assert buf.is_cuda and buf.is_contiguous()
     ms, units = C.c_float(), C.c_double()
-    _check(lib().moc_probe({"copy": 0, "mfma": 1}[kind], _ptr(buf), C.c_size_t(buf.numel() * buf.element_size()),
+    _check(lib().moc_probe({"copy": 0, "mfma": 1}[kind], _ptr(buf), buf.numel() * buf.element_size(),
                            int(iters), _stream(), C.byref(ms), C.byref(units)), "moc_probe")
     return ms.value, units.value

@@ -7,6 +7,7 @@
 #include <mutex>
 #include <cstring>
 #include <new>
+#include <cmath>
 #include <string>
 #include <unordered_set>
 #include <vector>
@@ -304,7 +305,7 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
                  o_wf = take((size_t)W * 4), o_wl = take((size_t)W * 4), o_aro = take((size_t)(W + 1) * 4),
                  o_ar = take(aranges.size() * sizeof(KeyRange)), o_at = take(atiles.size() * sizeof(AnchorTile)),
                  o_kv = take(kvitems.size() * sizeof(KvItem)), o_tt = take(ttiles.size() * sizeof(TextTile)),
-                 o_tm = take(textmask.size() * 4), o_cof = take((size_t)N * 4);
+                 o_tm = take(textmask.size() * 4), o_ntb = take((size_t)(C + 1) * 4), o_cof = take((size_t)N * 4);
     const size_t upload = o_cof;  // chunk_of is filled on the device
     std::vector<char> host(upload, 0);
     auto put = [&](size_t at, const void *src, size_t bytes) { if (bytes) std::memcpy(host.data() + at, src, bytes); };
@@ -319,6 +320,9 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
     put(o_kv, kvitems.data(), kvitems.size() * sizeof(KvItem));
     put(o_tt, ttiles.data(), ttiles.size() * sizeof(TextTile));
     put(o_tm, textmask.data(), textmask.size() * 4);
+    std::vector<int32_t> ntb(C + 1, 0);
+    for (int j = 0; j < C; ++j) ntb[j + 1] = ntb[j] + (kind[j] ? 0 : 1);
+    put(o_ntb, ntb.data(), (size_t)(C + 1) * 4);
 
     hipError_t e = hipMalloc(&m->d_base, o);
     if (e != hipSuccess) { delete m; return hip_fail(e, "hipMalloc(meta tables)"); }
@@ -335,6 +339,7 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
     m->d_kvitems = reinterpret_cast<KvItem *>(base + o_kv);
     m->d_text_tiles = reinterpret_cast<TextTile *>(base + o_tt);
     m->d_textmask = reinterpret_cast<uint32_t *>(base + o_tm);
+    m->d_ntb = reinterpret_cast<int32_t *>(base + o_ntb);
     m->d_chunk_of = reinterpret_cast<int32_t *>(base + o_cof);
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -391,9 +396,51 @@ int moc_route(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, 
     hipError_t e = moc::launch_pool(meta, B * H, d, dtype, k, pooled_k, kb_split, RL.Cpad, st);
     if (e != hipSuccess) return hip_fail(e, "pool kernel");
     if (topk > 0) {
-        e = moc::launch_route(meta, B * H, d, dtype, q, kb_split, RL.Cpad, topk, causal, sel, st);
+        e = moc::launch_route(meta, B * H, d, dtype, q, kb_split, RL.Cpad, topk, causal, sel, topk, st);
         if (e != hipSuccess) return hip_fail(e, "route kernel");
     }
+    return MOC_OK;
+}
+
+int moc_route_perturbed(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
+                        int32_t topk, int32_t causal, float p_max, float lambda, int32_t max_in, uint64_t seed,
+                        float *pooled_k, int32_t *sel, void *workspace, size_t workspace_bytes, void *stream) {
+    int rc = check_common(meta, B, H, d, topk, dtype);
+    if (rc) return rc;
+    if (max_in < 0 || topk + max_in > MOC_MAX_TOPK)
+        return fail(MOC_ERR_SHAPE, "need 0 <= max_in and topk + max_in <= MOC_MAX_TOPK");
+    if (!(p_max >= 0.f && p_max <= 1.f)) return fail(MOC_ERR_SHAPE, "p_max must lie in [0, 1]");
+    if (!(lambda >= 0.f) || !std::isfinite(lambda)) return fail(MOC_ERR_SHAPE, "lambda must be finite and >= 0");
+    const int width = topk + max_in;
+    rc = check_common(meta, B, H, d, width, dtype);     // the N * width limits of the attention calls
+    if (rc) return rc;
+    if (!q || !k || !pooled_k || (!sel && width > 0)) return fail(MOC_ERR_NULL, "q, k, pooled_k or sel is NULL");
+    if (misaligned(q) || misaligned(k) || misaligned(pooled_k) || misaligned(sel))
+        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    const moc::RouteWs RL = moc::route_ws_layout(meta, B * H, d, topk, dtype);
+    if (!workspace || workspace_bytes < RL.total) return fail(MOC_ERR_WORKSPACE, "route workspace too small");
+    if (misaligned(workspace)) return fail(MOC_ERR_ALIGN, "workspace must be 16-byte aligned");
+    // Poisson by inversion: thresholds floor(CDF(j) * 2^32), pmf(j) = pmf(j-1) * lambda / j
+    uint64_t thr[MOC_MAX_TOPK] = {};
+    {
+        double term = std::exp(-(double)lambda), cdf = 0.0;
+        for (int j = 0; j < max_in; ++j) {
+            if (j > 0) term = term * (double)lambda / j;
+            cdf += term;
+            thr[j] = (uint64_t)std::floor(std::min(cdf, 1.0) * 4294967296.0);
+        }
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    void *kb_split = static_cast<char *>(workspace) + RL.kb_split;
+    hipError_t e = moc::launch_pool(meta, B * H, d, dtype, k, pooled_k, kb_split, RL.Cpad, st);
+    if (e != hipSuccess) return hip_fail(e, "pool kernel");
+    if (width == 0) return MOC_OK;
+    if (topk > 0) {
+        e = moc::launch_route(meta, B * H, d, dtype, q, kb_split, RL.Cpad, topk, causal, sel, width, st);
+        if (e != hipSuccess) return hip_fail(e, "route kernel");
+    }
+    e = moc::launch_perturb(meta, B * H, topk, max_in, causal, p_max, thr, seed, sel, st);
+    if (e != hipSuccess) return hip_fail(e, "perturb kernel");
     return MOC_OK;
 }
 

@@ -46,6 +46,7 @@ struct moc_meta {
     int32_t *d_wlast = nullptr;      // [W] last chunk of window (inclusive)
     int32_t *d_chunk_of = nullptr;   // [N]
     uint32_t *d_textmask = nullptr;  // [ceil(C/32)] bit j%32 of word j/32 set: chunk j is text
+    int32_t *d_ntb = nullptr;        // [C+1] number of non-text chunks with index < j
     int32_t *d_arange_off = nullptr; // [W+1] into d_aranges
     moc::KeyRange *d_aranges = nullptr;
     moc::AnchorTile *d_atiles = nullptr;
@@ -69,6 +70,10 @@ struct ProfScope {
 };
 #define MOC_PROF(name, st) ::moc::ProfScope moc_prof_scope_(name, st)
 
+// Drop-off / drop-in on rows of width topk + max_in whose first topk columns hold the routed chunks.
+hipError_t launch_perturb(const moc_meta *m, int BH, int topk, int max_in, int causal, float p_max,
+                          const uint64_t *thr, uint64_t seed, int32_t *sel, hipStream_t st);
+
 // Machine probes (streaming copy, MFMA loop); see moc_probe.
 constexpr int kProbeMfmaGrid = 256;
 hipError_t launch_probe(int kind, void *buf, size_t bytes, int iters, hipStream_t st, hipEvent_t e0, hipEvent_t e1,
@@ -91,7 +96,7 @@ hipError_t launch_pool(const moc_meta *m, int BH, int d, int dtype, const void *
                        int Cpad, hipStream_t st);
 
 hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *kb_split, int Cpad,
-                        int topk, int causal, int32_t *sel, hipStream_t st);
+                        int topk, int causal, int32_t *sel, int sel_stride, hipStream_t st);
 
 // counts -> offsets -> inverse lists (per head and chunk: the queries that routed to it)
 hipError_t launch_build_lists(const moc_meta *m, int BH, int topk, const int32_t *sel, char *ws,

@@ -30,6 +30,7 @@ struct RouteArgs {
     const uint32_t *textmask;
     int32_t *sel;
     int N, C, Cpad, topk, causal;
+    int stride;                   // int32 words between consecutive rows of sel (>= topk)
 };
 
 constexpr int kQCap = 16;         // queue entries per lane
@@ -90,7 +91,7 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
     const int lim_lo = __shfl(limit, 0, 64);                            // smallest limit in the wave
     const int wf_lo = __shfl(wf, 0, 64), wl_hi = __shfl(wl, 31, 64);    // chunks that may be forced links in the wave
     const int topk = a.topk;
-    int32_t *out = a.sel + ((size_t)bh * N + ic) * topk;
+    int32_t *out = a.sel + ((size_t)bh * N + ic) * a.stride;
     if (ntiles == 0) {                                                  // no candidates at all
         if (valid && half == 0)
             for (int r = 0; r < topk; ++r) out[r] = -1;
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
 }
 
 hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *kb_split, int Cpad,
-                        int topk, int causal, int32_t *sel, hipStream_t st) {
+                        int topk, int causal, int32_t *sel, int sel_stride, hipStream_t st) {
     RouteArgs a{};
     a.q = q;
     a.split = static_cast<const bf16_t *>(kb_split);
@@ -253,6 +254,7 @@ hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void 
     a.textmask = m->d_textmask;
     a.sel = sel;
     a.N = m->N; a.C = m->C; a.Cpad = Cpad; a.topk = topk; a.causal = causal != 0;
+    a.stride = sel_stride;
     dim3 grid((m->N + 127) / 128, BH), block(256);
     MOC_PROF("route_topk", st);
 #define MOC_ROUTE(DD, TT, KK) route_kernel<DD, TT, KK><<<grid, block, 0, st>>>(a)
