@@ -152,6 +152,42 @@ int moc_route_perturbed(const moc_meta *meta, int32_t B, int32_t H, int32_t d, i
                         void *stream);
 
 /*
+ * Outer-loop context routing (App. "Outer Loop Context Routing"): a coarse
+ * selection of whole segments (e.g. shots) before the layer runs.
+ *   x            DEVICE in [N, D] of `dtype`: token features; D a multiple of 8.
+ *   seg_offsets  HOST [P+1]: segment j = rows [seg_offsets[j], seg_offsets[j+1]),
+ *                strictly increasing from 0 to N; P <= 4096.
+ *   mandatory    HOST [P] or NULL: non-zero marks segments that are always kept
+ *                (e.g. the global caption) and never compete.
+ *   g            the segment being generated; its mean feature is the query.
+ *   seg_mean     DEVICE out [P, D] fp32: arithmetic mean of each segment's rows.
+ *   scores       DEVICE out [P] fp32: <seg_mean[j], seg_mean[g]> for every j.
+ *   selected     HOST out [M]: the M best-scoring candidates, best first, ties
+ *                to the lower index, -1 padded. Candidates: segments other than
+ *                g that are not mandatory and, when causal != 0, precede g.
+ *   kept, n_kept HOST out [P], [1]: the segments of the reduced stream
+ *                (mandatory, selected and g) in ascending order.
+ *   workspace    DEVICE scratch of moc_outer_workspace_bytes(N, D, P) bytes.
+ * The call returns after the work on `stream` has finished (its results are
+ * needed on the host). Sums are formed in a fixed order: same input, same bits.
+ *
+ * moc_gather_rows builds the reduced stream of any row-major tensor: src is
+ * DEVICE [outer][n_src_rows][row_bytes], dst DEVICE [outer][sum of lengths]
+ * [row_bytes]; ranges HOST [n_ranges][2] = (first row, length) in the order the
+ * rows are to appear; row_bytes a multiple of 16; workspace DEVICE scratch of
+ * at least 16 * n_ranges bytes. Also returns after the copy has finished.
+ */
+int moc_outer_workspace_bytes(int32_t N, int32_t D, int32_t P, size_t *bytes);
+int moc_outer_route(int32_t N, int32_t D, int dtype, const void *x, int32_t P,
+                    const int32_t *seg_offsets, const int32_t *mandatory, int32_t g, int32_t M,
+                    int32_t causal, float *seg_mean, float *scores, int32_t *selected,
+                    int32_t *kept, int32_t *n_kept, void *workspace, size_t workspace_bytes,
+                    void *stream);
+int moc_gather_rows(int32_t outer, int32_t n_src_rows, int32_t row_bytes, const void *src,
+                    int32_t n_ranges, const int32_t *ranges, void *dst, void *workspace,
+                    size_t workspace_bytes, void *stream);
+
+/*
  * Stage (d) forward: o_i = softmax(q_i K_Omega^T * softmax_scale) V_Omega with
  * Omega(i) = tokens of all text chunks + the chunks of i's window + the chunks
  * listed in sel[i] (entries < 0 ignored). Forced links are not subject to the

@@ -23,7 +23,7 @@ MOC_BF16, MOC_F32 = 0, 1
 MOC_MAX_TOPK = 32
 
 SYMBOLS = ["moc_status_string", "moc_last_error", "moc_chunk_meta", "moc_meta_destroy", "moc_meta_copy_tables",
-           "moc_route_workspace_bytes", "moc_route", "moc_route_perturbed", "moc_attn_workspace_bytes", "moc_attn_fwd", "moc_attn_bwd",
+           "moc_route_workspace_bytes", "moc_route", "moc_route_perturbed", "moc_outer_workspace_bytes", "moc_outer_route", "moc_gather_rows", "moc_attn_workspace_bytes", "moc_attn_fwd", "moc_attn_bwd",
            "moc_prof_enable", "moc_prof_read", "moc_probe"]
 
 
@@ -61,6 +61,10 @@ def lib():
                                vp, vp, vp, vp, sz, vp]
     l.moc_route_perturbed.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, i32, i32, C.c_float, C.c_float, i32,
                                       C.c_uint64, vp, vp, vp, sz, vp]
+    l.moc_outer_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(sz)]
+    l.moc_outer_route.argtypes = [i32, i32, C.c_int, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp, vp, C.POINTER(i32),
+                                  vp, sz, vp]
+    l.moc_gather_rows.argtypes = [i32, i32, i32, vp, i32, vp, vp, vp, sz, vp]
     l.moc_probe.argtypes = [i32, vp, sz, i32, vp, C.POINTER(C.c_float), C.POINTER(C.c_double)]
     l.moc_prof_enable.argtypes = [C.c_int]
     l.moc_prof_read.argtypes = [i32, C.c_char_p, sz, C.POINTER(i32), C.POINTER(C.c_float)]
@@ -255,3 +259,43 @@ def probe(kind: str, buf: torch.Tensor, iters: int):
     _check(lib().moc_probe({"copy": 0, "mfma": 1}[kind], _ptr(buf), buf.numel() * buf.element_size(),
                            int(iters), _stream(), C.byref(ms), C.byref(units)), "moc_probe")
     return ms.value, units.value
+
+
+
+def outer_route(x: torch.Tensor, seg_offsets, mandatory, g: int, M: int, causal: bool = True):
+    """Outer-loop routing over features x [N, D] -> seg_mean [P, D] fp32, scores [P] fp32 (device),
+    selected [M] (numpy, best first, -1 padded), kept (ascending list of segments of the reduced stream)."""
+    assert x.is_cuda and x.dim() == 2
+    _need_contig(x)
+    N, D = x.shape
+    off = np.ascontiguousarray(seg_offsets, dtype=np.int32)
+    P = off.shape[0] - 1
+    mand = None if mandatory is None else np.ascontiguousarray(mandatory, dtype=np.int32)
+    nbytes = C.c_size_t()
+    _check(lib().moc_outer_workspace_bytes(N, D, P, C.byref(nbytes)), "moc_outer_workspace_bytes")
+    ws = torch.empty(max(nbytes.value, 16), dtype=torch.uint8, device=x.device)
+    mean = torch.empty(P, D, dtype=torch.float32, device=x.device)
+    scores = torch.empty(P, dtype=torch.float32, device=x.device)
+    selected = np.full(max(M, 1), -1, dtype=np.int32)
+    kept = np.zeros(P, dtype=np.int32)
+    n_kept = C.c_int32()
+    _check(lib().moc_outer_route(N, D, _dtype_code(x), _ptr(x), P, off.ctypes.data,
+                                 None if mand is None else mand.ctypes.data, int(g), int(M), int(bool(causal)),
+                                 _ptr(mean), _ptr(scores), selected.ctypes.data, kept.ctypes.data, C.byref(n_kept),
+                                 _ptr(ws), nbytes.value, _stream()), "moc_outer_route")
+    return mean, scores, selected[:max(M, 0)], kept[:n_kept.value].tolist()
+
+
+def gather_rows(src: torch.Tensor, ranges) -> torch.Tensor:
+    """src [..., N, d] (contiguous) -> [..., sum of lengths, d]: the rows of the listed (start, length) ranges."""
+    assert src.is_cuda and src.dim() >= 2
+    _need_contig(src)
+    rg = np.ascontiguousarray(ranges, dtype=np.int32).reshape(-1, 2)
+    n_src, dlast = src.shape[-2], src.shape[-1]
+    outer = int(np.prod(src.shape[:-2])) if src.dim() > 2 else 1
+    n_dst = int(rg[:, 1].sum())
+    dst = torch.empty(*src.shape[:-2], n_dst, dlast, dtype=src.dtype, device=src.device)
+    ws = torch.empty(max(16 * rg.shape[0], 16), dtype=torch.uint8, device=src.device)
+    _check(lib().moc_gather_rows(outer, n_src, dlast * src.element_size(), _ptr(src), rg.shape[0], rg.ctypes.data,
+                                 _ptr(dst), _ptr(ws), ws.numel(), _stream()), "moc_gather_rows")
+    return dst

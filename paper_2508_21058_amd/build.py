@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libmoc.so")
-UNITS = ["moc_api", "moc_pool", "moc_route", "moc_lists", "moc_attn_fwd", "moc_attn_bwd", "moc_probe", "moc_perturb"]
+UNITS = ["moc_api", "moc_pool", "moc_route", "moc_lists", "moc_attn_fwd", "moc_attn_bwd", "moc_probe", "moc_perturb", "moc_outer"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

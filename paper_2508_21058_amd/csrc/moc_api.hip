@@ -444,6 +444,114 @@ int moc_route_perturbed(const moc_meta *meta, int32_t B, int32_t H, int32_t d, i
     return MOC_OK;
 }
 
+namespace {
+struct OuterWs { size_t table, partial, total; };
+OuterWs outer_ws_layout(int N, int D, int P) {
+    OuterWs L{};
+    L.table = 0;
+    L.partial = align_up((size_t)(4 * (size_t)P + 4) * 4);
+    L.total = L.partial + ((size_t)N / 64 + (size_t)P + 1) * (size_t)D * 4;
+    return L;
+}
+int check_outer(int32_t N, int32_t D, int32_t P) {
+    if (N <= 0 || P <= 0 || P > N) return fail(MOC_ERR_SHAPE, "need 0 < P <= N");
+    if (P > moc::kMaxSegments) return fail(MOC_ERR_SHAPE, "too many segments");
+    if (D <= 0 || D % 8 != 0) return fail(MOC_ERR_SHAPE, "D must be a positive multiple of 8");
+    return MOC_OK;
+}
+}  // namespace
+
+int moc_outer_workspace_bytes(int32_t N, int32_t D, int32_t P, size_t *bytes) {
+    if (!bytes) return fail(MOC_ERR_NULL, "bytes is NULL");
+    int rc = check_outer(N, D, P);
+    if (rc) return rc;
+    *bytes = outer_ws_layout(N, D, P).total;
+    return MOC_OK;
+}
+
+int moc_outer_route(int32_t N, int32_t D, int dtype, const void *x, int32_t P, const int32_t *seg_offsets,
+                    const int32_t *mandatory, int32_t g, int32_t M, int32_t causal, float *seg_mean, float *scores,
+                    int32_t *selected, int32_t *kept, int32_t *n_kept, void *workspace, size_t workspace_bytes,
+                    void *stream) {
+    int rc = check_outer(N, D, P);
+    if (rc) return rc;
+    if (dtype != MOC_BF16 && dtype != MOC_F32) return fail(MOC_ERR_DTYPE, "dtype must be MOC_BF16 or MOC_F32");
+    if (!x || !seg_offsets || !seg_mean || !scores || !kept || !n_kept || (!selected && M > 0))
+        return fail(MOC_ERR_NULL, "a required pointer is NULL");
+    if (g < 0 || g >= P) return fail(MOC_ERR_SHAPE, "g must name a segment");
+    if (M < 0 || M > P) return fail(MOC_ERR_SHAPE, "need 0 <= M <= P");
+    if (seg_offsets[0] != 0 || seg_offsets[P] != N) return fail(MOC_ERR_OFFSETS, "segment offsets must run from 0 to N");
+    for (int j = 0; j < P; ++j)
+        if (seg_offsets[j + 1] <= seg_offsets[j]) return fail(MOC_ERR_OFFSETS, "segment offsets must be strictly increasing");
+    if (misaligned(x) || misaligned(seg_mean) || misaligned(workspace))
+        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    const OuterWs L = outer_ws_layout(N, D, P);
+    if (!workspace || workspace_bytes < L.total) return fail(MOC_ERR_WORKSPACE, "outer-route workspace too small");
+
+    // host table: offsets, first tile of each segment, candidate flags
+    const int tile = 64;
+    std::vector<int32_t> tab(4 * (size_t)P + 4, 0);
+    int32_t *h_off = tab.data(), *h_tb = h_off + (P + 1), *h_cand = h_tb + (P + 1);
+    int max_tiles = 0;
+    for (int j = 0; j < P; ++j) {
+        const int nt = (seg_offsets[j + 1] - seg_offsets[j] + tile - 1) / tile;
+        h_off[j] = seg_offsets[j];
+        h_tb[j + 1] = h_tb[j] + nt;
+        max_tiles = std::max(max_tiles, nt);
+        h_cand[j] = (j != g && !(mandatory && mandatory[j]) && (!causal || j < g)) ? 1 : 0;
+    }
+    h_off[P] = N;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    int32_t *d_tab = reinterpret_cast<int32_t *>(ws + L.table);
+    hipError_t e = hipMemcpyAsync(d_tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return hip_fail(e, "moc_outer_route table upload");
+    int32_t *d_sel = d_tab + (3 * (size_t)P + 2);
+    e = moc::launch_outer(D, dtype, x, P, max_tiles, g, M, d_tab, d_tab + (P + 1), d_tab + 2 * (P + 1),
+                          reinterpret_cast<float *>(ws + L.partial), seg_mean, scores, d_sel, st);
+    if (e != hipSuccess) return hip_fail(e, "outer-route kernels");
+    if (M > 0) {
+        e = hipMemcpyAsync(selected, d_sel, (size_t)M * 4, hipMemcpyDeviceToHost, st);
+        if (e != hipSuccess) return hip_fail(e, "moc_outer_route selection download");
+    }
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e, "moc_outer_route");
+    // reduced stream: mandatory segments, selected segments and g, in stream order
+    std::vector<char> in(P, 0);
+    in[g] = 1;
+    for (int j = 0; j < P; ++j) if (mandatory && mandatory[j]) in[j] = 1;
+    for (int r = 0; r < M; ++r) if (selected[r] >= 0) in[selected[r]] = 1;
+    int n = 0;
+    for (int j = 0; j < P; ++j) if (in[j]) kept[n++] = j;
+    *n_kept = n;
+    return MOC_OK;
+}
+
+int moc_gather_rows(int32_t outer, int32_t n_src_rows, int32_t row_bytes, const void *src, int32_t n_ranges,
+                    const int32_t *ranges, void *dst, void *workspace, size_t workspace_bytes, void *stream) {
+    if (outer <= 0 || n_src_rows <= 0 || n_ranges < 0) return fail(MOC_ERR_SHAPE, "outer, n_src_rows must be positive");
+    if (row_bytes <= 0 || row_bytes % 16 != 0) return fail(MOC_ERR_SHAPE, "row_bytes must be a positive multiple of 16");
+    if (n_ranges == 0) return MOC_OK;
+    if (!src || !dst || !ranges) return fail(MOC_ERR_NULL, "src, dst or ranges is NULL");
+    if (misaligned(src) || misaligned(dst) || misaligned(workspace))
+        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    if (!workspace || workspace_bytes < (size_t)n_ranges * 16) return fail(MOC_ERR_WORKSPACE, "need 16 bytes per range");
+    std::vector<int32_t> tab((size_t)n_ranges * 4, 0);
+    long long n_dst = 0;
+    for (int r = 0; r < n_ranges; ++r) {
+        const int32_t s0 = ranges[2 * r], len = ranges[2 * r + 1];
+        if (s0 < 0 || len <= 0 || (long long)s0 + len > n_src_rows) return fail(MOC_ERR_OFFSETS, "range outside the source");
+        if (n_dst + len >= (1LL << 31)) return fail(MOC_ERR_SHAPE, "reduced stream too long");
+        tab[4 * r] = s0; tab[4 * r + 1] = len; tab[4 * r + 2] = (int32_t)n_dst;
+        n_dst += len;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(workspace, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = moc::launch_gather(outer, n_src_rows, n_dst, row_bytes, src, dst, workspace, n_ranges, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);      // the table lives on this call's stack
+    return e == hipSuccess ? MOC_OK : hip_fail(e, "moc_gather_rows");
+}
+
 int moc_attn_workspace_bytes(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int32_t topk, int dtype,
                              int with_bwd, size_t *bytes) {
     if (!bytes) return fail(MOC_ERR_NULL, "bytes is NULL");

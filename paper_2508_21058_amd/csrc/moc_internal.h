@@ -74,6 +74,15 @@ struct ProfScope {
 hipError_t launch_perturb(const moc_meta *m, int BH, int topk, int max_in, int causal, float p_max,
                           const uint64_t *thr, uint64_t seed, int32_t *sel, hipStream_t st);
 
+// Outer-loop routing over [N, D] features: per-segment means, scores against segment g, top-M on the device.
+constexpr int kMaxSegments = 4096;
+hipError_t launch_outer(int D, int dtype, const void *x, int P, int max_tiles, int g, int M, const int32_t *d_seg_off,
+                        const int32_t *d_tile_base, const int32_t *d_cand, float *partial, float *mean,
+                        float *scores, int32_t *d_selected, hipStream_t st);
+// dst[o][..] = rows of src[o] listed by `n_ranges` records (src row, length, dst row, pad) on the device.
+hipError_t launch_gather(int outer, long long n_src_rows, long long n_dst_rows, int row_bytes, const void *src,
+                         void *dst, const void *d_ranges, int n_ranges, hipStream_t st);
+
 // Machine probes (streaming copy, MFMA loop); see moc_probe.
 constexpr int kProbeMfmaGrid = 256;
 hipError_t launch_probe(int kind, void *buf, size_t bytes, int iters, hipStream_t st, hipEvent_t e0, hipEvent_t e1,

@@ -8,7 +8,6 @@
 namespace moc {
 
 // Each lane moves 16 bytes per iteration; the grid strides over the buffer.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
                                                          size_t n16) {
     const size_t stride = (size_t)gridDim.x * 256;
