@@ -107,6 +107,53 @@ def cpu_baseline(lay, cfg, q, k, v, d_o, topk, budget_queries, causal=True):
                        f"pool + route of all {N} queries took another {t_route:.1f} s, not counted)")
 
 
+def bench_outer(args, lay, cfg, q, k, v, d_o, mi, mb, torch):
+    """Outer-loop routing of the last shot against the earlier ones (captions mandatory), then the gather."""
+    B, H, d, N = cfg["B"], cfg["H"], cfg["d"], lay.N
+    seg, cap = mi.shot_segments(lay)
+    g, M = len(seg) - 2, args.outer
+    x = k[0].permute(1, 0, 2).reshape(N, H * d).contiguous()       # token features [N, H d]
+    D = x.shape[1]
+
+    def step():
+        _, _, sel, kept = mb.outer_route(x, seg, cap, g, M, True)
+        ranges = [(int(seg[j]), int(seg[j + 1] - seg[j])) for j in kept]
+        return [mb.gather_rows(t, ranges) for t in (q, k, v, d_o)], kept
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    mb.prof_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        red, kept = step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern = {n: ms / max(c, 1) for n, (c, ms) in mb.prof_read().items()}
+    mb.prof_enable(False)
+    esz = x.element_size()
+    n_red = red[0].shape[2]
+    pool_bytes = N * D * esz + (N / 64 + len(seg)) * D * 4.0
+    gather_bytes = 2.0 * B * H * n_red * d * esz                     # per tensor: read + write
+    kernels = {"outer_partial": dict(ms=round(kern["outer_partial"], 4),
+                                     gbs=round(pool_bytes / kern["outer_partial"] / 1e6, 1)),
+               "outer_mean_score_select": dict(ms=round(kern["outer_mean_score_select"], 4)),
+               "gather_rows": dict(ms=round(kern["gather_rows"], 4), gbs=round(gather_bytes / kern["gather_rows"] / 1e6, 1))}
+    ach = kernels["outer_partial"]["gbs"]
+    total_bytes = pool_bytes + 4 * gather_bytes
+    print(json.dumps({
+        "metric": "outer_route_and_gather_GBs", "value": round(total_bytes / ms_step / 1e6, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32 sums of bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload} ({lay.name}): N={N} D={D} segments={len(seg) - 1} "
+                               f"(captions mandatory) M={M} g={g}; reduced stream {n_red} tokens x 4 tensors"},
+        "kernels": kernels,
+        "roofline": dict(kernel="outer_partial", bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s",
+                         frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, avg_ms=kernels["outer_partial"]["ms"]),
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -120,6 +167,9 @@ def main():
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--perturb", default=None, metavar="P_MAX,LAMBDA,MAX_IN",
                     help="route with context drop-off / drop-in (training-time regularisers); rows widen by MAX_IN")
+    ap.add_argument("--outer", type=int, default=None, metavar="M",
+                    help="time the outer-loop routing instead: segment means + top-M shots over [N, H d] features, "
+                         "then the gather of q, k, v, dO into the reduced stream")
     ap.add_argument("--inputs", default="S1", choices=["S1", "S2"],
                     help="S1: q, k, v, dO iid N(0,1) (graded); S2: chunk-coherent q and k (queries of a chunk select nearly the same chunks)")
     args = ap.parse_args()
@@ -148,6 +198,9 @@ def main():
         qc, kc = mi.coherent_qk(lay, B, H, d, args.seed)
         q, k = qc.to(tdt).to("cuda").contiguous(), kc.to(tdt).to("cuda").contiguous()
         del qc, kc
+
+    if args.outer is not None:
+        return bench_outer(args, lay, cfg, q, k, v, d_o, mi, mb, torch)
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
