@@ -167,6 +167,8 @@ def main():
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--perturb", default=None, metavar="P_MAX,LAMBDA,MAX_IN",
                     help="route with context drop-off / drop-in (training-time regularisers); rows widen by MAX_IN")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time its replays (launch gaps removed)")
     ap.add_argument("--outer", type=int, default=None, metavar="M",
                     help="time the outer-loop routing instead: segment means + top-M shots over [N, H d] features, "
                          "then the gather of q, k, v, dO into the reduced stream")
@@ -234,6 +236,24 @@ def main():
     for _ in range(args.warmup):
         sel = step()
     torch.cuda.synchronize()
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     mb.prof_enable(True)
     torch.cuda.synchronize()
@@ -342,6 +362,9 @@ def main():
         "keys_per_query": round(pairs / (BH * N), 1), "sparsity": round(1 - pairs / (BH * float(N) * N), 4),
         "kernels": kernels, "roofline": roof, "measured_peaks": measured,
     }
+    if graph_ms is not None:
+        out["graph_replay"] = {"ms_per_step": round(graph_ms, 3),
+                               "tflops": round(total_flops / (graph_ms * 1e-3) / 1e12, 2)}
     if args.cpu_queries > 0:
         out["cpu_baseline"] = cpu_baseline(lay, cfg, q, k, v, d_o, topk, args.cpu_queries, causal)
     print(json.dumps(out))

@@ -212,6 +212,9 @@ int moc_attn_fwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtyp
  *   dQ_i = scale * sum_t dS_it k_t,  dK_t = scale * sum_i dS_it q_i.
  * o, lse are the forward's outputs; dq, dk, dv [B,H,N,d] dtype are fully
  * overwritten. workspace must have been sized with with_bwd = 1.
+ * dq is bit-identical from call to call; dk and dv of routed chunks are summed
+ * over the routed queries in an order that may change between calls (fp32
+ * summation order only).
  */
 int moc_attn_bwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
                  const void *q, const void *k, const void *v, const void *o, const float *lse,

@@ -210,3 +210,55 @@ def test_probes_copy_exactly_and_report_plausible_rates():
     assert nbytes == 3 * 2.0 * (1 << 25) and 0 < nbytes / (ms * 1e-3) < 8.0e12
     ms, flops = mb.probe("mfma", buf, 2000)
     assert 0 < flops / (ms * 1e-3) < 2.6e15
+
+
+@pytest.mark.gpu
+def test_hot_path_replays_from_a_hip_graph():
+    """route + forward + backward captured once into a HIP graph (the calls allocate nothing and never
+    synchronise) and replayed with fresh inputs, with eager work and synchronisation between the replays.
+    sel, o, lse and dq must equal the eager result bit for bit; dk and dv sum over a chunk's routed queries in
+    the order the list builder's counters handed out, which varies from launch to launch, so they may differ
+    from another run by fp32 summation order (a bf16 rounding step at most)."""
+    lay = mi.multishot_layout(2, 32, 3, 128, 32, "frame")
+    B, H, d, topk, N = 1, 2, 128, 2, lay.N
+    meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
+    ws = mb.attn_workspace(meta, B, H, d, topk, torch.bfloat16, True)
+    stat = [torch.empty(B, H, N, d, dtype=torch.bfloat16, device="cuda") for _ in range(4)]     # q, k, v, dO
+    o, lse = torch.empty_like(stat[0]), torch.empty(B, H, N, dtype=torch.float32, device="cuda")
+    grads = tuple(torch.empty_like(stat[0]) for _ in range(3))
+
+    def run():
+        _, sel = mb.route(meta, stat[0], stat[1], topk, True)
+        mb.attn_fwd(meta, stat[0], stat[1], stat[2], sel, None, ws, (o, lse))
+        mb.attn_bwd(meta, stat[0], stat[1], stat[2], o, lse, stat[3], sel, None, ws, grads)
+        return sel
+
+    def load(seed):
+        for t, src in zip(stat, mi.qkv_do(B, H, N, d, seed, "cuda")):
+            t.copy_(src.to(torch.bfloat16))
+
+    load(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                                  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sel_g = run()
+    for seed in (1, 2, 3):
+        load(seed)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (sel_g, o, lse, *grads)]
+        sel_e = run()                                          # eager, same inputs
+        torch.cuda.synchronize()
+        for name, a, b in zip(("sel", "o", "lse", "dq", "dk", "dv"), got, (sel_e, o, lse, *grads)):
+            if name in ("dk", "dv"):
+                a, b = a.float(), b.float()
+                assert (a - b).abs().max() <= 2.0 ** -7 * b.abs().max(), name
+                assert ((a - b).abs() <= 2.0 ** -7 * b.abs() + 1e-6).all(), name
+            else:
+                assert torch.equal(a, b), name
+    meta.close()
