@@ -262,3 +262,18 @@ def test_hot_path_replays_from_a_hip_graph():
             else:
                 assert torch.equal(a, b), name
     meta.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d", [64, 128])
+def test_fp32_storage_ragged_layouts_two_samples(d):
+    """fp32 tensors (rounded to bf16 only where they enter a matrix-core product), B = 2, ragged chunks."""
+    lay = mi.random_layout(2000 + d, n_chunks=20, max_len=90, n_shots=2, text_prob=0.2, window="mixed")
+    run_case(lay, 2, 2, d, 3, torch.float32, seed=50 + d)
+
+
+@pytest.mark.gpu
+def test_widest_selection_k_32():
+    """k = MOC_MAX_TOPK with more than 32 candidates for late queries and fewer for early ones."""
+    lay = mi.multishot_layout(2, 8, 10, 48, 8, "frame")        # 122 chunks of 8 tokens
+    run_case(lay, 1, 2, 128, 32, torch.bfloat16, seed=61)
