@@ -221,6 +221,13 @@ __device__ __forceinline__ const void *uniform_ptr(const void *p) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
     return (const void *)(uintptr_t)(((uint64_t)hi << 32) | lo);
 }
+// Read-only table word at a wave-uniform index through the scalar cache (s_load): unlike a vector
+// load it does not enter the vector-memory counter that orders the asynchronous tile copies.
+__device__ __forceinline__ uint32_t uniform_load_u32(const uint32_t *table, int idx) {
+    const __attribute__((address_space(4))) uint32_t *t =
+        (const __attribute__((address_space(4))) uint32_t *)(uintptr_t)table;
+    return t[__builtin_amdgcn_readfirstlane(idx)];
+}
 __device__ __forceinline__ uint32_t lds_address(const void *p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)p;
 }

@@ -35,18 +35,22 @@ struct RouteArgs {
 
 constexpr int kQCap = 16;         // queue entries per lane
 
-// sorted insert, strict: an equal score stays behind the entries already there
+// sorted insert (descending), strict: an equal score stays behind the entries already there.
+// Position p takes the median of (val[p-1], val[p], x): the shifted neighbour if x passed it, x if it
+// lands here, else what it held; the index follows with one comparison per position.
 template <int KMAX>
 __device__ __forceinline__ void topk_insert(float (&val)[KMAX], int (&idx)[KMAX], float x, int xi) {
+    bool above = false;                 // x > val[p-1]
+    float pv = INFINITY;                // val[p-1] before this insert
+    int pi = -1;
 #pragma unroll
     for (int p = 0; p < KMAX; ++p) {
-        const bool sw = x > val[p];
+        const bool here = x > val[p];
         const float tv = val[p];
         const int ti = idx[p];
-        val[p] = sw ? x : tv;
-        idx[p] = sw ? xi : ti;
-        x = sw ? tv : x;
-        xi = sw ? ti : xi;
+        val[p] = __builtin_amdgcn_fmed3f(pv, tv, x);
+        idx[p] = above ? pi : (here ? xi : ti);
+        above = here; pv = tv; pi = ti;
     }
 }
 
@@ -65,19 +69,29 @@ __device__ __forceinline__ void topk_insert_tie(float (&val)[KMAX], int (&idx)[K
     }
 }
 
+// Four waves x 32 queries per workgroup, two workgroups per CU, two staged tiles of pooled keys (one
+// in use, one in flight). The pass is bound by the selection's vector instructions, not by the
+// latency of the tile copies: eight waves with three stages (one workgroup per CU) measured 13 %
+// slower, because a barrier per tile then couples twice as many waves whose queue drains fall on
+// different tiles.
+constexpr int kRouteThreads = 256;
+constexpr int kRouteStages = 2;
+
 template <int D, typename T, int KMAX>
-__global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
+__global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void route_kernel(RouteArgs a) {
     constexpr int KS = D / 16;
     constexpr int NQ = sizeof(T) == 2 ? 1 : 3;       // query planes
     constexpr int PB = 32 * D * 2;                   // bytes of one plane tile (32 chunks)
     constexpr int TB = 3 * PB;                       // bytes of one staged tile
-    __shared__ __attribute__((aligned(1024))) char smem[2 * TB];
-    __shared__ float qs[kQCap][256];
-    __shared__ int32_t qidx[kQCap][256];
+    constexpr int NWV = kRouteThreads / 64;
+    constexpr int QPW = kRouteThreads / 2;           // queries per workgroup
+    __shared__ __attribute__((aligned(1024))) char smem[kRouteStages * TB];
+    __shared__ float qs[kQCap][kRouteThreads];
+    __shared__ int32_t qidx[kQCap][kRouteThreads];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
     const int bh = blockIdx.y, N = a.N, C = a.C;
-    const int q0 = blockIdx.x * 128;
+    const int q0 = blockIdx.x * QPW;
     const int i = q0 + wave * 32 + l32;
     const bool valid = i < N;
     const int ic = valid ? i : N - 1;
@@ -86,7 +100,7 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
     const int wf = a.wfirst[w], wl = a.wlast[w];
     const int limit = a.causal ? cq : C;                               // candidates have index < limit
     // queries ascend with the lane, so do chunk, window and limit
-    const int lim_wg = a.causal ? a.chunk_of[min(q0 + 127, N - 1)] : C;  // uniform: largest limit in the workgroup
+    const int lim_wg = __builtin_amdgcn_readfirstlane(a.causal ? a.chunk_of[min(q0 + QPW - 1, N - 1)] : C);  // uniform: largest limit in the workgroup
     const int ntiles = (lim_wg + 31) >> 5;
     const int lim_lo = __shfl(limit, 0, 64);                            // smallest limit in the wave
     const int wf_lo = __shfl(wf, 0, 64), wl_hi = __shfl(wl, 31, 64);    // chunks that may be forced links in the wave
@@ -130,15 +144,43 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
             }
         }
     }
+    // The query fragments are consumed here, before the first tile copy is issued: the waits the
+    // compiler needs for their loads then sit in front of the loop, not inside it, where they would
+    // also wait for the tile copies in flight.
+#pragma unroll
+    for (int qa = 0; qa < NQ; ++qa)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            u32x4 w = __builtin_bit_cast(u32x4, qf[qa][s]);
+            asm volatile("" : "+v"(w));
+            qf[qa][s] = __builtin_bit_cast(bf16x8, w);
+        }
     LaneOffs<D> lo;
     lo.init(lane);
 
-    TileLoader<D, bf16_t, 32> ld(tid);
+    // Copies of one staged tile (3 planes x 32 rows), spread over the eight waves: a wave instruction
+    // moves 1 KB (512 / D rows). Every wave issues the same number of copies per tile so that one
+    // vmcnt bound fits all (with D = 64 the last four waves repeat a copy of the first four).
+    constexpr int RPI = 512 / D, NI = 32 / RPI, TOT = 3 * NI, PW = (TOT + NWV - 1) / NWV;
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    const int rlo = lane / (D / 8), cgp = lane % (D / 8);
     const bf16_t *sp = a.split + (size_t)bh * 3 * a.Cpad * D;
     auto issue = [&](int t, int buf) {
+        const uint32_t at = lds_address(smem + buf * TB);
 #pragma unroll
-        for (int p = 0; p < 3; ++p)
-            ld.issue_rows(sp + ((size_t)p * a.Cpad + t * 32) * D, 32, reinterpret_cast<bf16_t *>(smem + buf * TB + p * PB));
+        for (int p = 0; p < PW; ++p) {
+            const int n = (uwave + NWV * p) % TOT;
+            const int plane = n / NI, sub = n % NI;
+            const int row = sub * RPI + rlo;
+            const int cg = cgp ^ SwTile<D>::sw(row);
+            const bf16_t *src = sp + ((size_t)plane * a.Cpad + (size_t)t * 32) * D;
+            async_copy16_at(src, (uint32_t)(row * D + cg * 8) * 2u, at + plane * PB + sub * 1024);
+        }
+    };
+    // tile t + 1 has landed once at most the copies of the tiles after it are still in flight
+    constexpr int DIST = kRouteStages - 1;           // tiles issued ahead of the one in use
+    auto landed = [&](int t_next) {
+        if (DIST > 1 && t_next + DIST - 1 < ntiles) wait_vmcnt<(DIST - 1) * PW>(); else wait_vmcnt<0>();
     };
 
     // scores of tile t for this lane: 16 chunks, ineligible ones set to -inf
@@ -161,7 +203,7 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
                 }
             }
         const int j0 = t * 32;
-        const uint32_t tm = a.textmask[t];
+        const uint32_t tm = uniform_load_u32(a.textmask, t);
         // fast path: the whole tile is a candidate for every query of the wave
         const bool clean = tm == 0 && j0 + 32 <= lim_lo && (j0 + 32 <= wf_lo || j0 > wl_hi);
         if (!clean) {
@@ -200,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
     auto scan = [&](auto cur, int t) {
         constexpr int CUR = decltype(cur)::value;
         const bool more = t + 1 < ntiles;
-        if (more) issue(t + 1, CUR ^ 1);
+        if (t + DIST < ntiles) issue(t + DIST, (CUR + DIST) % kRouteStages);
         const f32x16 sc = scores(cur, t);
         int np = 0;
 #pragma unroll
@@ -215,16 +257,18 @@ __global__ __launch_bounds__(256, 2) void route_kernel(RouteArgs a) {
                 ++cnt;
             }
         }
-        if (more) { ld.commit(nullptr); __syncthreads(); }
+        if (more) { landed(t + 1); __syncthreads(); }
         return more;
     };
-    __syncthreads();
-    issue(0, 0);
-    ld.commit(nullptr);
+#pragma unroll
+    for (int u = 0; u < DIST; ++u)
+        if (u < ntiles) issue(u, u);
+    landed(0);
     __syncthreads();
     for (int t = 0;;) {
         if (!scan(IC<0>{}, t++)) break;
-        if (!scan(IC<1>{}, t++)) break;
+        if (!scan(IC<1 % kRouteStages>{}, t++)) break;
+        if (kRouteStages > 2 && !scan(IC<2 % kRouteStages>{}, t++)) break;
     }
     drain();
 
@@ -255,7 +299,7 @@ hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void 
     a.sel = sel;
     a.N = m->N; a.C = m->C; a.Cpad = Cpad; a.topk = topk; a.causal = causal != 0;
     a.stride = sel_stride;
-    dim3 grid((m->N + 127) / 128, BH), block(256);
+    dim3 grid((m->N + kRouteThreads / 2 - 1) / (kRouteThreads / 2), BH), block(kRouteThreads);
     MOC_PROF("route_topk", st);
 #define MOC_ROUTE(DD, TT, KK) route_kernel<DD, TT, KK><<<grid, block, 0, st>>>(a)
 #define MOC_ROUTE_K(DD, TT)                         \
