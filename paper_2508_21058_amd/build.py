@@ -18,7 +18,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libmoc.so")
 UNITS = ["moc_api", "moc_pool", "moc_route", "moc_lists", "moc_attn_fwd", "moc_attn_bwd", "moc_probe", "moc_perturb", "moc_outer"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+# -Wno-inline-asm: the tile-copy asm lists m0 (which it sets) as clobbered; clang warns that m0 is reserved
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
