@@ -88,3 +88,38 @@ def test_probe_rejects_bad_arguments_before_any_launch():
     assert lib.moc_probe(0, C.c_void_p(0x1004), C.c_size_t(64), 1, None, C.byref(ms), C.byref(units)) == -8
     assert lib.moc_probe(0, fake, C.c_size_t(16), 1, None, C.byref(ms), C.byref(units)) == -7
     assert lib.moc_probe(1, fake, C.c_size_t(4096), 1, None, C.byref(ms), C.byref(units)) == -7
+
+
+def test_outer_route_and_gather_reject_bad_arguments_on_the_host():
+    """Every check below fails before the first GPU call, so it runs without a GPU."""
+    lib = mb.lib()
+    nbytes = C.c_size_t()
+    assert lib.moc_outer_workspace_bytes(100, 16, 4, C.byref(nbytes)) == 0 and nbytes.value > 0
+    assert lib.moc_outer_workspace_bytes(100, 12, 4, C.byref(nbytes)) == -2        # D not a multiple of 8
+    assert lib.moc_outer_workspace_bytes(100, 16, 0, C.byref(nbytes)) == -2        # no segment
+    assert lib.moc_outer_workspace_bytes(100, 16, 5000, C.byref(nbytes)) == -2     # more segments than rows
+    assert lib.moc_outer_workspace_bytes(100, 16, 4, None) == -1
+    fake = C.c_void_p(0x1000)                     # never dereferenced
+    off = np.array([0, 10, 40, 100], np.int32)
+    sel = np.zeros(3, np.int32); kept = np.zeros(3, np.int32); nk = C.c_int32()
+
+    def call(off_, g=1, M=1, x=fake, dtype=0, D=16, ws_bytes=1 << 30):
+        return lib.moc_outer_route(100, D, dtype, x, 3, off_.ctypes.data, None, g, M, 1, fake, fake, sel.ctypes.data,
+                                   kept.ctypes.data, C.byref(nk), fake, ws_bytes, None)
+
+    assert call(off, g=3) == -2 and call(off, g=-1) == -2                           # g names no segment
+    assert call(off, M=4) == -2 and call(off, M=-1) == -2
+    assert call(np.array([0, 10, 10, 100], np.int32)) == -3                         # empty segment
+    assert call(np.array([0, 10, 40, 99], np.int32)) == -3                          # does not end at N
+    assert call(off, dtype=7) == -6
+    assert call(off, x=None) == -1
+    assert call(off, x=C.c_void_p(0x1004)) == -8
+    assert call(off, ws_bytes=16) == -7
+
+    rg = np.array([[0, 5], [90, 20]], np.int32)                                     # second range runs past the source
+    assert lib.moc_gather_rows(1, 100, 64, fake, 2, rg.ctypes.data, fake, fake, 64, None) == -3
+    ok = np.array([[0, 5], [90, 10]], np.int32)
+    assert lib.moc_gather_rows(1, 100, 60, fake, 2, ok.ctypes.data, fake, fake, 64, None) == -2   # row bytes % 16
+    assert lib.moc_gather_rows(1, 100, 64, fake, 2, ok.ctypes.data, fake, fake, 16, None) == -7   # table does not fit
+    assert lib.moc_gather_rows(1, 100, 64, None, 2, ok.ctypes.data, fake, fake, 64, None) == -1
+    assert lib.moc_gather_rows(1, 100, 64, fake, 0, None, fake, fake, 0, None) == 0               # nothing to do

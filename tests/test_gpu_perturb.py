@@ -142,3 +142,18 @@ def test_attention_accepts_the_wider_rows():
     check_close("dk", dk.float().cpu().numpy(), dk_ref)
     check_close("dv", dv.float().cpu().numpy(), dv_ref)
     meta.close()
+
+
+def test_bad_regulariser_arguments_are_refused():
+    lay = mi.multishot_layout(1, 8, 2, 32, 16, "chunk")
+    meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
+    q = torch.zeros(1, 1, lay.N, 64, dtype=torch.bfloat16, device="cuda")
+    for kw in (dict(p_max=1.5), dict(p_max=-0.1), dict(lam=-1.0), dict(lam=float("inf")), dict(max_in=-1),
+               dict(topk=20, max_in=13)):
+        args = dict(topk=2, causal=True, p_max=0.5, lam=1.0, max_in=2, seed=1)
+        args.update(kw)
+        with pytest.raises(mb.MocError) as e:
+            mb.route_perturbed(meta, q, q, args["topk"], args["causal"], args["p_max"], args["lam"], args["max_in"],
+                               args["seed"])
+        assert e.value.status == -2, kw
+    meta.close()
