@@ -54,9 +54,11 @@ struct Philox {
 constexpr int kPerturbThreads = 128;
 
 __global__ __launch_bounds__(kPerturbThreads) void perturb_kernel(PerturbArgs a) {
-    // per lane: routed chunks (slots 0..31), then the sorted excluded ranks (up to 64)
-    __shared__ int32_t ent[MOC_MAX_TOPK][kPerturbThreads];
-    __shared__ int32_t ex[2 * MOC_MAX_TOPK][kPerturbThreads];
+    // per lane: the routed chunks (topk slots), then the sorted excluded ranks (topk + max_in slots);
+    // sized at launch so that small rows leave room for many workgroups per CU
+    extern __shared__ int32_t lds[];
+    int32_t (*ent)[kPerturbThreads] = reinterpret_cast<int32_t (*)[kPerturbThreads]>(lds);
+    int32_t (*ex)[kPerturbThreads] = ent + a.topk;
     const int tid = threadIdx.x;
     const int i = blockIdx.x * kPerturbThreads + tid;
     if (i >= a.N) return;
@@ -142,7 +144,8 @@ hipError_t launch_perturb(const moc_meta *m, int BH, int topk, int max_in, int c
     for (int j = 0; j < max_in; ++j) a.thr[j] = thr[j];
     dim3 grid((m->N + kPerturbThreads - 1) / kPerturbThreads, BH);
     MOC_PROF("route_perturb", st);
-    perturb_kernel<<<grid, kPerturbThreads, 0, st>>>(a);
+    const size_t lds_bytes = (size_t)(2 * topk + max_in) * kPerturbThreads * sizeof(int32_t);   // <= 48 KB
+    perturb_kernel<<<grid, kPerturbThreads, lds_bytes, st>>>(a);
     return hipGetLastError();
 }
 
