@@ -33,7 +33,7 @@ struct RouteArgs {
     int stride;                   // int32 words between consecutive rows of sel (>= topk)
 };
 
-constexpr int kQCap = 16;         // queue entries per lane
+constexpr int kQCap = 15;         // queue entries per lane (plus one spill row: 2 x 16 KB of LDS for 256 lanes)
 
 // sorted insert (descending), strict: an equal score stays behind the entries already there.
 // Position p takes the median of (val[p-1], val[p], x): the shifted neighbour if x passed it, x if it
@@ -86,8 +86,8 @@ __global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void r
     constexpr int NWV = kRouteThreads / 64;
     constexpr int QPW = kRouteThreads / 2;           // queries per workgroup
     __shared__ __attribute__((aligned(1024))) char smem[kRouteStages * TB];
-    __shared__ float qs[kQCap][kRouteThreads];
-    __shared__ int32_t qidx[kQCap][kRouteThreads];
+    __shared__ float qs[kQCap + 1][kRouteThreads];       // row kQCap takes what does not fit
+    __shared__ int32_t qidx[kQCap + 1][kRouteThreads];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
     const int bh = blockIdx.y, N = a.N, C = a.C;
@@ -207,13 +207,15 @@ __global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void r
         // fast path: the whole tile is a candidate for every query of the wave
         const bool clean = tm == 0 && j0 + 32 <= lim_lo && (j0 + 32 <= wf_lo || j0 > wl_hi);
         if (!clean) {
+            // One 32-bit word per lane, bit b = chunk j0 + b is a candidate of this lane's query:
+            // below the causal limit, outside the own window [wf, wl], not text. The lane then
+            // tests its 16 bits, (r >> 2) * 8 + half * 4 + (r & 3), at compile-time positions.
+            auto below = [](int n) { return n >= 32 ? 0xffffffffu : (n <= 0 ? 0u : ((1u << n) - 1u)); };
+            const uint32_t okm = below(limit - j0) & (below(wf - j0) | ~below(wl - j0 + 1)) & ~tm;
+            const uint32_t mine = okm >> (half * 4);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int bit = (r >> 2) * 8 + half * 4 + (r & 3);
-                const int j = j0 + bit;
-                const bool ok = j < limit && (j < wf || j > wl) && !((tm >> bit) & 1u);
-                if (!ok) acc[r] = -INFINITY;
-            }
+            for (int r = 0; r < 16; ++r)
+                if (!((mine >> ((r >> 2) * 8 + (r & 3))) & 1u)) acc[r] = -INFINITY;
         }
         return acc;
     };
@@ -244,19 +246,32 @@ __global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void r
         const bool more = t + 1 < ntiles;
         if (t + DIST < ntiles) issue(t + DIST, (CUR + DIST) % kRouteStages);
         const f32x16 sc = scores(cur, t);
-        int np = 0;
+        // Branch-free append: every score is written at the lane's cursor and the cursor moves only if
+        // the score passes, so a later score overwrites a rejected one. Entries past the capacity go
+        // to a spill row; if any lane spilled, the appends of that half tile are taken back, the queues
+        // drained (which also raises the bounds) and the half appended again: 8 scores always fit then.
+        const int jb = t * 32 + half * 4;
+        auto append = [&](auto first) {
+            constexpr int R0 = decltype(first)::value;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) np += sc[r] >= tau ? 1 : 0;
-        if (__any(cnt + np > kQCap)) drain();   // make room (the bound may rise, fewer scores pass)
-        const int j0 = t * 32;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            if (sc[r] >= tau) {
-                qs[cnt][tid] = sc[r];
-                qidx[cnt][tid] = j0 + (r >> 2) * 8 + half * 4 + (r & 3);
-                ++cnt;
+            for (int r = R0; r < R0 + 8; ++r) {
+                const int slot = min(cnt, kQCap);
+                qs[slot][tid] = sc[r];
+                qidx[slot][tid] = jb + (r >> 2) * 8 + (r & 3);
+                cnt += sc[r] >= tau ? 1 : 0;
             }
-        }
+        };
+        auto append_checked = [&](auto first) {
+            const int before = cnt;
+            append(first);
+            if (__any(cnt > kQCap)) {
+                cnt = before;
+                drain();
+                append(first);
+            }
+        };
+        append_checked(IC<0>{});
+        append_checked(IC<8>{});
         if (more) { landed(t + 1); __syncthreads(); }
         return more;
     };
