@@ -79,3 +79,23 @@ def test_reduced_rows_keep_stream_order():
     rows = ou.reduced_rows(off, [0, 2, 3])
     assert rows.tolist() == [0, 1, 2, 4, 5, 6, 7, 8, 9, 10]
     assert (np.diff(rows) > 0).all()
+
+
+def test_segments_and_reduced_layout_bookkeeping():
+    """Layout helpers used with the outer loop: captions are segments of their own, a shot's video chunks
+    form one segment, and the reduced layout keeps chunk lengths, shots, windows and caption spans."""
+    import moc_inputs as mi
+    lay = mi.multishot_layout(3, 8, 2, 16, 8, "frame")
+    seg, cap = mi.shot_segments(lay)
+    assert seg.tolist() == [0, 8, 40, 48, 80, 88, 120] and cap.tolist() == [1, 0, 1, 0, 1, 0]
+    kept = [0, 2, 4, 5]
+    red = mi.reduce_layout(lay, seg, kept)
+    rows = ou.reduced_rows(seg, kept)
+    assert red.N == len(rows) == 8 + 8 + 8 + 32
+    # every reduced chunk is an original chunk, moved as a whole
+    src_chunk = np.searchsorted(lay.offsets, rows[red.offsets[:-1]], side="right") - 1
+    assert (np.diff(red.offsets) == np.diff(lay.offsets)[src_chunk]).all()
+    assert (red.shot == lay.shot[src_chunk]).all() and (red.window == lay.window[src_chunk]).all()
+    assert red.text_spans.tolist() == [[0, 8], [8, 16], [16, 24]]
+    with pytest.raises(ValueError):
+        mi.reduce_layout(lay, np.array([0, 12, 120], np.int32), [0])     # 12 is not a chunk boundary
