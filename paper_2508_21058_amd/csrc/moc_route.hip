@@ -86,8 +86,7 @@ __global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void r
     constexpr int NWV = kRouteThreads / 64;
     constexpr int QPW = kRouteThreads / 2;           // queries per workgroup
     __shared__ __attribute__((aligned(1024))) char smem[kRouteStages * TB];
-    __shared__ float qs[kQCap + 1][kRouteThreads];       // row kQCap takes what does not fit
-    __shared__ int32_t qidx[kQCap + 1][kRouteThreads];
+    __shared__ u32x2 queue[kQCap + 1][kRouteThreads];    // (score bits, chunk) pairs; row kQCap takes what does not fit
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
     const int bh = blockIdx.y, N = a.N, C = a.C;
@@ -234,8 +233,9 @@ __global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void r
         for (int o = 32; o >= 1; o >>= 1) mx = max(mx, __shfl_xor(mx, o, 64));
         for (int e = 0; e < mx; ++e) {
             const bool has = e < cnt;
-            const float x = has ? qs[e][tid] : -INFINITY;
-            const int xi = has ? qidx[e][tid] : -1;
+            const u32x2 ent = queue[e][tid];
+            const float x = has ? __builtin_bit_cast(float, ent[0]) : -INFINITY;
+            const int xi = has ? (int)ent[1] : -1;
             topk_insert<KMAX>(val, idx, x, xi);
         }
         cnt = 0;
@@ -256,8 +256,9 @@ __global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void r
 #pragma unroll
             for (int r = R0; r < R0 + 8; ++r) {
                 const int slot = min(cnt, kQCap);
-                qs[slot][tid] = sc[r];
-                qidx[slot][tid] = jb + (r >> 2) * 8 + (r & 3);
+                const float x = sc[r];      // (a bit cast straight from the vector element picks element 0)
+                const u32x2 ent = {__builtin_bit_cast(uint32_t, x), (uint32_t)(jb + (r >> 2) * 8 + (r & 3))};
+                queue[slot][tid] = ent;
                 cnt += sc[r] >= tau ? 1 : 0;
             }
         };
