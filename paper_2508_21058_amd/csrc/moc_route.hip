@@ -240,6 +240,10 @@ __global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void r
         }
         cnt = 0;
         tau = fmaxf(tau, val[KMAX - 1]);     // once the list is full its tail bounds the k-th best
+        // The other half-wave holds the other 16 chunks of every tile for the same query: the k-th best
+        // of either half is a lower bound of the k-th best of both, so the larger of the two bounds
+        // serves both halves and about half as many scores reach the queues.
+        tau = fmaxf(tau, xhalf(tau));
     };
     auto scan = [&](auto cur, int t) {
         constexpr int CUR = decltype(cur)::value;
