@@ -234,7 +234,8 @@ __global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void r
         for (int e = 0; e < mx; ++e) {
             const bool has = e < cnt;
             const u32x2 ent = queue[e][tid];
-            const float x = has ? __builtin_bit_cast(float, ent[0]) : -INFINITY;
+            const uint32_t bits = ent[0];
+            const float x = has ? __builtin_bit_cast(float, bits) : -INFINITY;
             const int xi = has ? (int)ent[1] : -1;
             topk_insert<KMAX>(val, idx, x, xi);
         }
