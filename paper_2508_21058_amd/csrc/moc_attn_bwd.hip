@@ -274,6 +274,146 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(FwdArgs a) {
     store_rows_bf16<D>(smem, wave, lane, dqacc, a.scale, row_valid ? (int)prow : -1, a.po);
 }
 
+// Routed dQ items, chunk-stationary (bf16 storage, chunks of at most kChunkRows keys): as in the
+// forward, K and V of one chunk stay in LDS (K is read both as a row operand for S and transposed
+// for dQ from the same swizzled tile) and the eight waves stream the chunk's inverse list through
+// them independently, 32 list entries at a time: no barrier and no staging inside a chunk, K / V
+// fetched once per group of query tiles instead of once per query tile. Each (query, link) pair
+// writes its partial dQ to its slot; the forced-link items add the slots afterwards.
+template <int D>
+__global__ __launch_bounds__(512, 1) void attn_bwd_dq_chunk_kernel(FwdArgs a) {
+    typedef bf16_t T;
+    constexpr int KS = D / 16, DB = D / 32;
+    constexpr int RB = D * 2;                     // bytes per row
+    constexpr int KBYTES = kChunkRows * RB;
+    constexpr int VBYTES = (kChunkRows + 32) * RB;
+    constexpr int RPI = 1024 / RB;                // rows per copy instruction
+    __shared__ __attribute__((aligned(1024))) char smem[KBYTES + VBYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    const int N = a.N, C = a.C;
+    const int groups_per_head = (a.items_per_head + kGroupTiles - 1) / kGroupTiles;
+    int logical;
+    if (!xcd_remap((long long)groups_per_head * a.BH, logical)) return;
+    const int bh = logical / groups_per_head;
+    const int32_t *toff = a.tile_off + (size_t)bh * (C + 1);
+    const int32_t *loff = a.list_off + (size_t)bh * (C + 1);
+    int t0 = (logical - bh * groups_per_head) * kGroupTiles;
+    const int t1 = min(t0 + kGroupTiles, toff[C]);
+    if (t0 >= t1) return;
+    int j;
+    {
+        int lo = 0, hi = C;   // largest j with toff[j] <= t0
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (toff[mid] <= t0) lo = mid; else hi = mid;
+        }
+        j = lo;
+    }
+    const char *qbase = static_cast<const char *>(a.q) + (size_t)bh * N * RB;
+    const char *dobase = static_cast<const char *>(a.d_o) + (size_t)bh * N * RB;
+    const char *kbase = static_cast<const char *>(a.k) + (size_t)bh * N * RB;
+    const char *vbase = static_cast<const char *>(a.v) + (size_t)bh * N * RB;
+    const float c = a.scale_log2;
+    LaneOffs<D> lo;
+    lo.init(lane);
+    const int rlo = lane / (D / 8), cgp = lane % (D / 8);
+
+    while (t0 < t1) {
+        while (toff[j + 1] <= t0) ++j;            // chunk of tile t0
+        const int te = min(t1, toff[j + 1]);      // this chunk's tiles in the group: [t0, te)
+        const int key0 = a.off[j], len = a.off[j + 1] - key0;
+        const int nhalf = (len + 31) >> 5;        // 32-key half tiles
+        // ---- K / V of the chunk -> LDS (rows past the end repeat the last row: finite, masked as keys)
+        {
+            const int nk = (min(nhalf * 32, kChunkRows) + RPI - 1) / RPI;
+            for (int i = wave; i < 2 * nk; i += 8) {
+                const bool isk = i < nk;
+                const int ii = isk ? i : i - nk;
+                const int row = ii * RPI + rlo;
+                const uint32_t off = (uint32_t)(min(row, len - 1) * RB + ((cgp ^ SwTile<D>::sw(row)) << 4));
+                async_copy16((isk ? kbase : vbase) + (size_t)key0 * RB, off, smem + (isk ? 0 : KBYTES) + ii * 1024);
+            }
+            wait_vmcnt<0>();
+            __syncthreads();
+        }
+        // ---- the chunk's list entries covered by tiles [t0, te)
+        const int cnt = loff[j + 1] - loff[j];
+        const int q_first = (t0 - toff[j]) * kBM;
+        const int nq = min(cnt, (te - toff[j]) * kBM) - q_first;
+        const size_t lbase = (size_t)bh * N * a.topk + loff[j] + q_first;
+        const int32_t *entries = a.qlist + lbase;
+        const float2 *stats = reinterpret_cast<const float2 *>(a.gstats2) + lbase;
+        // software pipeline over the wave's blocks: the list entry and the statistics of the next
+        // block are fetched before the key tiles of the current one; its Q and dO fragments are
+        // fetched into the registers of the current ones once the last key tile is done, so their
+        // latency runs under the stores of the current block's partial dQ
+        auto load_qdo = [&](int ent, bf16x8 *qf, bf16x8 *dof) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                qf[s] = Io<T>::load8(reinterpret_cast<const T *>(qbase + (size_t)(ent >> 5) * RB) + s * 16 + half * 8);
+                dof[s] = Io<T>::load8(reinterpret_cast<const T *>(dobase + (size_t)(ent >> 5) * RB) + s * 16 + half * 8);
+            }
+        };
+        bf16x8 qf[KS], dof[KS];
+        int e = 0;
+        float2 st2 = make_float2(0.f, 0.f);
+        if (wave * 32 < nq) {
+            const int pos = min(wave * 32 + l32, nq - 1);
+            e = entries[pos];
+            st2 = stats[pos];                                 // (lse * log2 e, delta)
+            load_qdo(e, qf, dof);
+        }
+        for (int blk = wave; blk * 32 < nq; blk += 8) {
+            const bool more = (blk + 8) * 32 < nq;
+            int e_next = e;
+            float2 st_next = st2;
+            if (more) {
+                const int pn = min((blk + 8) * 32 + l32, nq - 1);
+                e_next = entries[pn];
+                st_next = stats[pn];
+            }
+            f32x16 dqacc[DB];
+#pragma unroll
+            for (int b = 0; b < DB; ++b) dqacc[b] = zero16();
+            for (int h = 0; h < nhalf; h += 2) {
+                const char *tile = smem + h * 32 * RB;
+                const int valid = len - h * 32;
+                dq_half_tile<D, 0, KBYTES, 0>(tile, lo, qf, dof, dqacc, c, st2.x, st2.y, valid, lane);
+                if (valid > 32) dq_half_tile<D, 0, KBYTES, 32>(tile, lo, qf, dof, dqacc, c, st2.x, st2.y, valid, lane);
+            }
+            const int e_cur = e;
+            if (more) load_qdo(e_next, qf, dof);
+            e = e_next;
+            st2 = st_next;
+            // 16-byte stores: the two half-waves hold adjacent 4-feature pieces of the same query and
+            // exchange them (lower half: features [16 u, 16 u + 8), upper half: [16 u + 8, 16 u + 16))
+            if (blk * 32 + l32 < nq) {
+                const size_t prow = ((size_t)bh * N + (e_cur >> 5)) * a.slots + (e_cur & 31);
+                T *dst = a.po + prow * D + half * 8;
+                const float sc = a.scale;
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const int g = 2 * u;
+                        const uint32_t x0 = pack_bf16(dqacc[b][4 * g] * sc, dqacc[b][4 * g + 1] * sc);
+                        const uint32_t x1 = pack_bf16(dqacc[b][4 * g + 2] * sc, dqacc[b][4 * g + 3] * sc);
+                        const uint32_t y0 = pack_bf16(dqacc[b][4 * g + 4] * sc, dqacc[b][4 * g + 5] * sc);
+                        const uint32_t y1 = pack_bf16(dqacc[b][4 * g + 6] * sc, dqacc[b][4 * g + 7] * sc);
+                        const auto r0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+                        const auto r1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+                        const u32x4 w = {r0[0], r1[0], r0[1], r1[1]};
+                        *reinterpret_cast<u32x4 *>(dst + b * 32 + u * 16) = w;
+                    }
+            }
+        }
+        t0 = te;
+        if (t0 < t1) __syncthreads();             // every wave is done with this chunk's K / V
+    }
+}
+
 template <int D, typename T>
 __global__ __launch_bounds__(256) void dq_merge_kernel(const bf16_t *__restrict__ part,
                                                        const int32_t *__restrict__ sel, int N, int C, int topk,
@@ -1252,7 +1392,16 @@ static hipError_t bwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, KvArgs &kv
     if (a.topk > 0) {
         a.items_per_head = (m->N * a.topk + kBM - 1) / kBM + m->C;
         MOC_PROF("attn_bwd_dq_routed", st);
-        attn_bwd_dq_kernel<D, T, MODE_ROUTED><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a);
+        bool chunk_path = false;
+        if constexpr (sizeof(T) == 2) {
+            if (m->max_chunk_len <= kChunkRows) {
+                chunk_path = true;
+                const int groups = (a.items_per_head + kGroupTiles - 1) / kGroupTiles;
+                attn_bwd_dq_chunk_kernel<D><<<dim3(xcd_grid((long long)groups * BH)), dim3(512), 0, st>>>(a);
+            }
+        }
+        if (!chunk_path)
+            attn_bwd_dq_kernel<D, T, MODE_ROUTED><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a);
     }
     { MOC_PROF("attn_bwd_dq_forced", st);
     a.items_per_head = m->n_atiles;
@@ -1282,6 +1431,7 @@ hipError_t launch_attn_bwd(const moc_meta *m, int BH, int d, int dtype, const vo
     a.qlist = reinterpret_cast<const int32_t *>(ws + L.qlist);
     a.lse = lse;
     a.delta = reinterpret_cast<const float *>(ws + L.delta);
+    a.gstats2 = reinterpret_cast<const float *>(ws + L.gstats2);
     KvArgs kv{};
     kv.q = q; kv.k = k; kv.v = v; kv.d_o = d_o;
     kv.lse = lse; kv.delta = a.delta;

@@ -26,11 +26,17 @@ struct FwdArgs {
     // backward only
     const void *d_o;
     const float *lse, *delta;
+    const float *gstats2;   // [BH, N*topk] pairs (lse * log2 e, delta) in inverse-list order
     // forced-link forward items with the merge fused into their epilogue
     const int32_t *sel;     // [BH, N, topk] selections (which routed slots are in use)
     void *o_out;            // [BH, N, D] final output
     float *lse_out;         // [BH, N] final log-sum-exp
 };
+
+// Chunk-stationary routed items (forward and dQ pass): a workgroup keeps the keys and values of one
+// chunk in LDS and serves a group of that chunk's query tiles from them.
+constexpr int kChunkRows = 288;       // resident keys (K region; the V region holds 32 rows more)
+constexpr int kGroupTiles = 16;       // query tiles (of kBM list entries) per workgroup
 
 // The GPU has 8 XCDs with private L2 caches and hands consecutive workgroups to
 // them round-robin. Work lists are ordered so that neighbours share K/V (or

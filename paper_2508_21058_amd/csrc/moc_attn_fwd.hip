@@ -317,8 +317,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(FwdArgs a) {
 // output and its log-sum-exp into the slot of the (query, link) pair. Inside a
 // chunk there is no barrier and no shared staging, so one wave's memory and
 // LDS latencies are covered by the other wave of its SIMD.
-constexpr int kChunkRows = 288;       // resident keys (K region; the V region holds 32 rows more, see below)
-constexpr int kGroupTiles = 16;
 
 template <int D>
 __global__ __launch_bounds__(512, 1) void attn_fwd_chunk_kernel(FwdArgs a) {
