@@ -223,7 +223,7 @@ def random_layout(seed: int, n_chunks: int = 12, max_len: int = 40, n_shots: int
     return _finish(f"rand{seed}", offs, shot, win, spans, seed=seed)
 
 
-# ---- the five workloads named in the benchmark spec -------------------------------
+# ---- the named workloads ------------------------------------------------------
 
 def config_layout(cfg: str, window: Optional[str] = None, chunk: Optional[int] = None) -> Layout:
     if cfg == "tiny":        # 64 text + 1 shot x 4 frames x 256 tokens, chunk 64, own-chunk window

@@ -1,4 +1,4 @@
-"""Parity at the benchmark's full sizes, in the launch configuration bench.py
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
 times (all heads, bf16, same seeded device-generated inputs), on sampled
 outputs the oracle can compute one by one:
 
@@ -93,12 +93,12 @@ def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=Non
 
 
 def test_single_shot_config_forward_backward():
-    """BASELINE configs 2/3: 512 text + 21 x 1560 tokens, chunk 260, frame window, k=5, H=24, d=128."""
+    """Single-shot configuration: 512 text + 21 x 1560 tokens, chunk 260, frame window, k=5, H=24, d=128."""
     _run("single", None, head=5, n_sample=384, with_text_chunk=True)
 
 
 def test_eight_shot_config_frame_window():
-    """BASELINE config 4 (benchmark workload): 8 x (256 + 9 x 1560) tokens, frame window, k=8."""
+    """Eight-shot configuration (benchmark workload): 8 x (256 + 9 x 1560) tokens, frame window, k=8."""
     _run("eight", "frame", head=17, n_sample=384, with_text_chunk=False)
 
 
@@ -108,7 +108,7 @@ def test_eight_shot_config_shot_window():
 
 
 def test_sweep_config_chunk_130():
-    """BASELINE config 5 (32 shots, N = 457,472) at chunk 130: 3,488 chunks, 2-key tail tiles, k=8."""
+    """Sweep configuration (32 shots, N = 457,472) at chunk 130: 3,488 chunks, 2-key tail tiles, k=8."""
     _run("sweep", "frame", head=7, n_sample=192, with_text_chunk=False, chunk=130)
 
 

@@ -109,7 +109,7 @@ def run_case(lay, B, H, d, topk, dtype, seed, causal=True, check_route=True):
 
 
 def test_tiny_config_fp32_storage():
-    """BASELINE config 1: B=1, H=2, d=64, fp32 storage, 64 text + 4 x 256 video tokens, chunk 64, k=2."""
+    """Tiny configuration: B=1, H=2, d=64, fp32 storage, 64 text + 4 x 256 video tokens, chunk 64, k=2."""
     run_case(mi.config_layout("tiny"), 1, 2, 64, 2, torch.float32, seed=11)
 
 
