@@ -23,8 +23,11 @@ from tests.test_gpu_parity import check_close, check_sel
 pytestmark = pytest.mark.gpu
 
 
-def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=None, lay=None, cfg=None, n_chunks=2):
-    cfg = cfg or mi.CONFIGS[workload]
+def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=None, lay=None, cfg=None, n_chunks=2,
+         topk=None):
+    cfg = dict(cfg or mi.CONFIGS[workload])
+    if topk is not None:
+        cfg["topk"] = topk
     lay = lay or mi.config_layout(workload, window=window, chunk=chunk)
     B, H, d, topk, N = cfg["B"], cfg["H"], cfg["d"], cfg["topk"], lay.N
     causal = bool(cfg.get("causal", True))
@@ -139,3 +142,12 @@ def test_chunks_of_10240_tokens():
     lay = mi.stream_layout(2, 64, 12000, 10240, "shot")
     cfg = dict(B=1, H=2, d=128, dtype="bf16", topk=5)
     _run(None, None, head=1, n_sample=64, with_text_chunk=False, lay=lay, cfg=cfg, n_chunks=1)
+
+
+def test_sweep_config_chunk_260_k16():
+    """Sweep configuration at its widest selection: 16 routed chunks per query, rows of 16 slots."""
+    _run("sweep", "frame", head=19, n_sample=128, with_text_chunk=False, chunk=260, topk=16, n_chunks=1)
+
+
+def test_sweep_config_chunk_260_k2():
+    _run("sweep", "frame", head=4, n_sample=128, with_text_chunk=False, chunk=260, topk=2, n_chunks=1)

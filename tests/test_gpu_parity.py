@@ -56,11 +56,13 @@ def to_dev(x, dtype):
     return torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(dtype).contiguous()
 
 
-def run_case(lay, B, H, d, topk, dtype, seed, causal=True, check_route=True):
+def run_case(lay, B, H, d, topk, dtype, seed, causal=True, check_route=True, coherent=False):
     """Full pipeline on the GPU vs the oracle; attention is also checked with
     the oracle's selection injected so stage (d) is isolated from ties."""
     N = lay.N
     q, k, v, d_o = mi.qkv_do(B, H, N, d, seed, "cpu", bf16_round=True)
+    if coherent:           # chunk-coherent q and k: the queries of a chunk select nearly the same chunks
+        q, k = mi.coherent_qk(lay, B, H, d, seed)
     qn, kn, vn, don = (t.numpy().astype(np.float64) for t in (q, k, v, d_o))
     L = mo.OracleLayout.from_layout(lay)
     ref = mo.moc_layer(L, qn, kn, vn, topk, causal, don)
@@ -277,3 +279,14 @@ def test_widest_selection_k_32():
     """k = MOC_MAX_TOPK with more than 32 candidates for late queries and fewer for early ones."""
     lay = mi.multishot_layout(2, 8, 10, 48, 8, "frame")        # 122 chunks of 8 tokens
     run_case(lay, 1, 2, 128, 32, torch.bfloat16, seed=61)
+
+
+@pytest.mark.gpu
+def test_chunk_coherent_inputs_very_uneven_lists():
+    """Chunk-coherent q and k: all queries of a chunk route to the same few chunks, so some inverse lists
+    hold many chunks' worth of queries and others are empty."""
+    lay = mi.multishot_layout(3, 16, 4, 192, 32, "frame")       # 75 chunks
+    ref = run_case(lay, 1, 2, 128, 3, torch.bfloat16, seed=71, coherent=True)
+    sel = ref["sel"][0, 0]
+    counts = np.bincount(sel[sel >= 0], minlength=lay.C)
+    assert (counts == 0).sum() >= 3 and counts.max() >= 8 * 32              # empty lists and very long ones
