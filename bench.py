@@ -29,6 +29,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+# vector instructions per matrix instruction in the score + top-k pass, from the counter run recorded in
+# profiles/moc_kernels_eight_shot_frame_window_counters.txt (SQ_INSTS_VALU / SQ_INSTS_MFMA)
+ROUTE_VALU_PER_MFMA = 23.4
 
 
 def layout_counts(lay, sel, chunk_of_t, topk, causal=True):
@@ -110,7 +113,7 @@ def cpu_baseline(lay, cfg, q, k, v, d_o, topk, budget_queries, causal=True):
 def bench_outer(args, lay, cfg, q, k, v, d_o, mi, mb, torch):
     """Outer-loop routing of the last shot against the earlier ones (captions mandatory), then the gather."""
     B, H, d, N = cfg["B"], cfg["H"], cfg["d"], lay.N
-    seg, cap = mi.shot_segments(lay)
+    seg, cap = mb.outer_segments(lay.offsets, lay.shot, lay.text_spans)
     g, M = len(seg) - 2, args.outer
     x = k[0].permute(1, 0, 2).reshape(N, H * d).contiguous()       # token features [N, H d]
     D = x.shape[1]
@@ -172,6 +175,8 @@ def main():
     ap.add_argument("--outer", type=int, default=None, metavar="M",
                     help="time the outer-loop routing instead: segment means + top-M shots over [N, H d] features, "
                          "then the gather of q, k, v, dO into the reduced stream")
+    ap.add_argument("--no-secondary", dest="secondary", action="store_false",
+                    help="skip the secondary rows (shot window, S2 inputs) that the default run of the benchmark workload adds")
     ap.add_argument("--inputs", default="S1", choices=["S1", "S2"],
                     help="S1: q, k, v, dO iid N(0,1) (graded); S2: chunk-coherent q and k (queries of a chunk select nearly the same chunks)")
     args = ap.parse_args()
@@ -204,18 +209,68 @@ def main():
     if args.outer is not None:
         return bench_outer(args, lay, cfg, q, k, v, d_o, mi, mb, torch)
 
+    perturb = None
+    if args.perturb:
+        p_max, lam, max_in = args.perturb.split(",")
+        perturb = (float(p_max), float(lam), int(max_in))
+    tensors = (q, k, v, d_o)
+    out = measure(args, lay, cfg, tensors, args.steps, args.warmup, perturb, args.graph, True, mi, mb, torch)
+
+    # secondary rows of the same build, each a whole step on its own workload, fewer steps, no CPU leg:
+    # the benchmark layout with the whole shot as the local window (the paper's multi-shot forced link), and the
+    # primary workload on chunk-coherent inputs (S2)
+    if args.secondary and args.workload == "eight" and not args.perturb and args.inputs == "S1":
+        sec = {}
+        lay2 = mi.config_layout("eight", window="shot" if lay.meta.get("window") != "shot" else "frame", chunk=args.chunk)
+        r = measure(args, lay2, cfg, tensors, 4, 2, None, False, False, mi, mb, torch)
+        sec[f"window_{lay2.meta.get('window')}"] = secondary_row(r)
+        qc, kc = mi.coherent_qk(lay, B, H, d, args.seed, device="cuda")
+        r = measure(args, lay, cfg, (qc.to(tdt).contiguous(), kc.to(tdt).contiguous(), v, d_o), 4, 2, None, False, False,
+                    mi, mb, torch, inputs="S2")
+        del qc, kc
+        sec["inputs_S2_chunk_coherent"] = secondary_row(r)
+        out["secondary"] = sec
+    if args.cpu_queries > 0:
+        out["cpu_baseline"] = cpu_baseline(lay, cfg, q, k, v, d_o, topk, args.cpu_queries, causal)
+    print(json.dumps(out))
+
+
+def secondary_row(r):
+    return {"workload": r["config"]["workload"], "inputs": r["config"]["inputs"], "ms_per_step": r["ms_per_step"],
+            "tflops": r["value"], "frac_of_bf16_mfma_peak": r["frac_of_bf16_mfma_peak"],
+            "keys_per_query": r["keys_per_query"], "sparsity": r["sparsity"],
+            "kernels_ms": {n: row["ms"] for n, row in r["kernels"].items()}}
+
+
+def read_traffic(workload, window):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by what the
+    counter reads for a copy of known size); the figures live in profiles/, written from a run of this script."""
+    tfile = os.path.join(ROOT, "profiles", "moc_kernels_eight_shot_frame_window.txt")
+    out = {}
+    if os.path.exists(tfile):
+        key = f"traffic {workload}:{window}:"
+        for line in open(tfile):
+            if line.startswith(key):
+                name, val = line[len(key):].split("=")
+                out[name.strip()] = float(val)
+    return out, "profiles/" + os.path.basename(tfile)
+
+
+def measure(args, lay, cfg, tensors, steps, warmup, perturb, use_graph, with_probes, mi, mb, torch, inputs=None):
+    """Times `steps` whole steps (route -> forward -> backward) on one layout and returns the bench line."""
+    q, k, v, d_o = tensors
+    B, H, d, topk, N = cfg["B"], cfg["H"], cfg["d"], cfg["topk"], lay.N
+    if args.topk is not None:
+        topk = args.topk
+    causal = bool(cfg.get("causal", True))
+    tdt = q.dtype
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
     torch.cuda.synchronize()
     meta_ms = (time.perf_counter() - t0) * 1e3
 
-    perturb = None
-    width = topk
-    if args.perturb:
-        p_max, lam, max_in = args.perturb.split(",")
-        perturb = (float(p_max), float(lam), int(max_in))
-        width = topk + perturb[2]
+    width = topk + (perturb[2] if perturb else 0)
     ws = mb.attn_workspace(meta, B, H, d, width, tdt, True)
     o = torch.empty_like(q); lse = torch.empty(B, H, N, dtype=torch.float32, device="cuda")
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
@@ -229,15 +284,16 @@ def main():
         if ev: ev[1].record()
         mb.attn_fwd(meta, q, k, v, sel, None, ws, (o, lse))
         if ev: ev[2].record()
-        mb.attn_bwd(meta, q, k, v, o, lse, d_o, sel, None, ws, (dq, dk, dv))
+        # the backward of a training step follows its forward: the lists built there are used again
+        mb.attn_bwd(meta, q, k, v, o, lse, d_o, sel, None, ws, (dq, dk, dv), after_fwd=True)
         if ev: ev[3].record()
         return sel
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         sel = step()
     torch.cuda.synchronize()
     graph_ms = None
-    if args.graph:
+    if use_graph:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -250,21 +306,21 @@ def main():
         graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for s in range(args.steps):
+        for s in range(steps):
             graph.replay()
         torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        graph_ms = (time.perf_counter() - t0) * 1e3 / steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
     mb.prof_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for s in range(args.steps):
+    for s in range(steps):
         sel = step(evs[s])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     kern = mb.prof_read()
     mb.prof_enable(False)
-    ms_step = wall * 1e3 / args.steps
+    ms_step = wall * 1e3 / steps
     stage_all = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in evs])
     stage = stage_all.mean(0)
 
@@ -275,26 +331,38 @@ def main():
     fwd_flops = 4.0 * d * pairs
     total_flops = 3.5 * fwd_flops
     esz = 2 if tdt == torch.bfloat16 else 4
-    # algorithmic work per kernel launch: (kind, amount)
+    row = N * d * esz * BH                    # one [B, H, N, d] tensor
+    # algorithmic work per kernel launch: (kind, amount, algorithmic HBM bytes)
     alg = {
-        "attn_fwd_forced": ("flop", 4.0 * d * pairs_f), "attn_fwd_routed": ("flop", 4.0 * d * pairs_r),
-        "attn_bwd_dkdv": ("flop", 8.0 * d * pairs),
-        "attn_bwd_dq_forced": ("flop", 2.0 * d * pairs_f), "attn_bwd_dq_routed": ("flop", 2.0 * d * pairs_r),
-        "pool": ("byte", BH * (N * d * esz + lay.C * d * 4.0)),
-        "route_topk": ("byte", BH * (N * d * esz + lay.C * d * 4.0 + N * topk * 4.0)),
-        "route_perturb": ("byte", BH * N * (topk + width) * 4.0),
+        "attn_fwd_forced": ("flop", 4.0 * d * pairs_f, None), "attn_fwd_routed": ("flop", 4.0 * d * pairs_r, None),
+        "attn_fwd": ("flop", 4.0 * d * pairs, 4.0 * row),                        # q, k, v in; o out
+        "attn_bwd_dkdv": ("flop", 8.0 * d * pairs, 6.0 * row),                   # q, k, v, dO in; dk, dv out
+        "attn_bwd_dq_forced": ("flop", 2.0 * d * pairs_f, None), "attn_bwd_dq_routed": ("flop", 2.0 * d * pairs_r, None),
+        "attn_bwd_dq": ("flop", 2.0 * d * pairs, 5.0 * row),                     # q, k, v, dO in; dq out
+        "pool": ("byte", BH * (N * d * esz + lay.C * d * 4.0), None),
+        "route_topk": ("byte", BH * (N * d * esz + lay.C * d * 4.0 + N * topk * 4.0), None),
+        "route_perturb": ("byte", BH * N * (topk + width) * 4.0, None),
     }
+    traffic, tsrc = read_traffic(args.workload, lay.meta.get("window"))
     kernels = {}
     for name, (cnt, ms) in kern.items():
         per = ms / max(cnt, 1)
-        row = dict(ms=round(per, 4))
+        krow = dict(ms=round(per, 4))
         if name in alg:
-            kind, amt = alg[name]
+            kind, amt, _ = alg[name]
             if kind == "flop":
-                row["tflops"] = round(amt / (per * 1e-3) / 1e12, 2)
+                krow["tflops"] = round(amt / (per * 1e-3) / 1e12, 2)
             else:
-                row["gbs"] = round(amt / (per * 1e-3) / 1e9, 1)
-        kernels[name] = row
+                krow["gbs"] = round(amt / (per * 1e-3) / 1e9, 1)
+        kernels[name] = krow
+    # measured HBM bytes against algorithmic bytes, per pass (the routed and forced kernels of a pass share its tensors)
+    traffic_ratio = {}
+    for pas, parts in (("attn_fwd", ("attn_fwd_routed", "attn_fwd_forced")), ("attn_bwd_dkdv", ("attn_bwd_dkdv",)),
+                       ("attn_bwd_dq", ("attn_bwd_dq_routed", "attn_bwd_dq_forced"))):
+        if all(p_ in traffic for p_ in parts):
+            meas = sum(traffic[p_] for p_ in parts)
+            traffic_ratio[pas] = {"measured_GB": round(meas, 2), "algorithmic_GB": round(alg[pas][2] / 1e9, 2),
+                                  "ratio": round(meas * 1e9 / alg[pas][2], 2)}
     dom = max((n for n in kernels if n in alg), key=lambda n: kernels[n]["ms"])
     if alg[dom][0] == "flop":
         ach = alg[dom][1] / (kernels[dom]["ms"] * 1e-3) / 1e12
@@ -304,26 +372,23 @@ def main():
         ach = alg[dom][1] / (kernels[dom]["ms"] * 1e-3) / 1e9
         roof = dict(kernel=dom, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                     frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, avg_ms=kernels[dom]["ms"])
-    # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled); see profiles/
-    tfile = os.path.join(ROOT, "profiles", "moc_kernels_eight_shot_frame_window.txt")
-    if os.path.exists(tfile):
-        key = f"traffic {args.workload}:{lay.meta.get('window')}:{dom} ="
-        for line in open(tfile):
-            if line.startswith(key):
-                roof["traffic"] = {"hbm_GB_per_launch": float(line.split("=")[1]), "source": "profiles/" + os.path.basename(tfile)}
+    if dom in traffic:
+        roof["traffic"] = {"hbm_GB_per_launch": traffic[dom], "source": tsrc}
 
-    # what this GPU sustains on a plain streaming copy and on a bare MFMA loop (context for the fractions above)
-    pbuf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-    c_ms, c_bytes = mb.probe("copy", pbuf, 20)
-    m_ms, m_flops = mb.probe("mfma", pbuf, 100000)
-    del pbuf
-    measured = {"hbm_copy_GBs": round(c_bytes / (c_ms * 1e-3) / 1e9, 1),
-                "bf16_mfma_TFLOPs": round(m_flops / (m_ms * 1e-3) / 1e12, 1)}
-    roof["frac_of_measured"] = round(roof["achieved"] / (measured["bf16_mfma_TFLOPs"] if roof["bound"] == "mfma"
-                                                         else measured["hbm_copy_GBs"]), 4)
+    measured = None
+    if with_probes:
+        # what this GPU sustains on a plain streaming copy and on a bare MFMA loop (context for the fractions above)
+        pbuf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        c_ms, c_bytes = mb.probe("copy", pbuf, 20)
+        m_ms, m_flops = mb.probe("mfma", pbuf, 100000)
+        del pbuf
+        measured = {"hbm_copy_GBs": round(c_bytes / (c_ms * 1e-3) / 1e9, 1),
+                    "bf16_mfma_TFLOPs": round(m_flops / (m_ms * 1e-3) / 1e12, 1)}
+        roof["frac_of_measured"] = round(roof["achieved"] / (measured["bf16_mfma_TFLOPs"] if roof["bound"] == "mfma"
+                                                             else measured["hbm_copy_GBs"]), 4)
 
-    # routing: bytes as asked, and the score contraction's rate on the unit it runs on (three bf16 MFMA planes
-    # per candidate score); the top-k pass is bound by that work, not by HBM, once a query has hundreds of candidates
+    # routing: bytes as asked, and the score contraction's rate on the unit it runs on (three bf16 matrix
+    # products per fp32-accurate score). Which resource bounds the pass is read off the measured rates.
     routing = {}
     if "pool" in kernels:
         routing["pool_GBs"] = kernels["pool"]["gbs"]
@@ -333,8 +398,17 @@ def main():
         routing["score_topk_GBs"] = kernels["route_topk"]["gbs"]
         routing["score_topk_frac_of_hbm_peak"] = round(kernels["route_topk"]["gbs"] / PEAK_HBM_GBS, 4)
         routing["score_TFLOPs_algorithmic"] = round(2.0 * d * eligible * BH / (r_ms * 1e-3) / 1e12, 2)
+        # executed on the matrix cores: whole 32-chunk tiles up to the causal limit, three bf16 planes per score
+        tiles = float(np.ceil(np.repeat(np.arange(lay.C), np.diff(lay.offsets)) / 32.0).sum()) if causal else \
+            float(N) * np.ceil(lay.C / 32.0)
+        exec_flops = 3.0 * 2.0 * d * 32.0 * tiles * BH
+        routing["score_TFLOPs_executed_bf16"] = round(exec_flops / (r_ms * 1e-3) / 1e12, 1)
+        routing["score_frac_of_bf16_mfma_peak"] = round(exec_flops / (r_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)
         routing["candidates_per_query"] = round(eligible / N, 1)
-        routing["bound"] = "mfma+selection" if eligible / N >= 300 else "hbm"
+        routing["valu_per_mfma_instruction"] = ROUTE_VALU_PER_MFMA
+        hb, mf = routing["score_topk_frac_of_hbm_peak"], routing["score_frac_of_bf16_mfma_peak"]
+        routing["bound"] = ("selection (vector instructions): neither HBM nor the matrix cores are near their peak"
+                            if max(hb, mf) < 0.4 else ("hbm" if hb >= mf else "mfma"))
     # the same step priced as a dense causal attention of the same length (2 N^2 d per head forward, x3.5)
     dense_flops = 3.5 * 2.0 * float(N) * N * d * BH
     dense = {"flops": dense_flops, "equivalent_TFLOPs": round(dense_flops / (ms_step * 1e-3) / 1e12, 1),
@@ -342,12 +416,12 @@ def main():
 
     out = {
         "metric": "routed_attn_tflops_fwd_bwd", "value": round(total_flops / (ms_step * 1e-3) / 1e12, 2),
-        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if tdt == torch.bfloat16 else "f32(bf16 mfma)", "data": "synthetic",
         "config": {"workload": f"{args.workload} ({lay.name}): B={B} H={H} N={N} d={d} C={lay.C} "
                                f"chunk={lay.meta.get('chunk')} window={lay.meta.get('window')} topk={topk} {'causal' if causal else 'non-causal'}",
-                   "inputs": ("S1 iid N(0,1) rounded to bf16, seeded" if args.inputs == "S1" else
+                   "inputs": ("S1 iid N(0,1) rounded to bf16, seeded" if (inputs or args.inputs) == "S1" else
                               "S2 chunk-coherent q and k (rho = 0.9, planted earlier target chunk), v and dO iid, seeded"),
                    "pass": "route + attn fwd + attn bwd",
                    **({"perturb": f"drop-off p_max={perturb[0]} drop-in lambda={perturb[1]} max_in={perturb[2]}"}
@@ -360,14 +434,16 @@ def main():
         "stage_ms_min": [round(float(x), 3) for x in stage_all.min(0)],
         "routing": routing, "dense_equivalent": dense,
         "keys_per_query": round(pairs / (BH * N), 1), "sparsity": round(1 - pairs / (BH * float(N) * N), 4),
-        "kernels": kernels, "roofline": roof, "measured_peaks": measured,
+        "kernels": kernels, "traffic_ratio": traffic_ratio, "roofline": roof,
     }
+    if measured:
+        out["measured_peaks"] = measured
     if graph_ms is not None:
         out["graph_replay"] = {"ms_per_step": round(graph_ms, 3),
                                "tflops": round(total_flops / (graph_ms * 1e-3) / 1e12, 2)}
-    if args.cpu_queries > 0:
-        out["cpu_baseline"] = cpu_baseline(lay, cfg, q, k, v, d_o, topk, args.cpu_queries, causal)
-    print(json.dumps(out))
+    meta.close()
+    del ws, o, lse, dq, dk, dv
+    return out
 
 
 if __name__ == "__main__":

@@ -176,7 +176,31 @@ int moc_route_perturbed(const moc_meta *meta, int32_t B, int32_t H, int32_t d, i
  * [row_bytes]; ranges HOST [n_ranges][2] = (first row, length) in the order the
  * rows are to appear; row_bytes a multiple of 16; workspace DEVICE scratch of
  * at least 16 * n_ranges bytes. Also returns after the copy has finished.
+ *
+ * Layout bookkeeping of the outer loop, host arrays only, no device work:
+ * moc_outer_segments cuts the stream into the segments the outer router sees:
+ *   a new segment starts wherever a caption span starts or ends and wherever
+ *   the shot id changes, so every caption span is a segment of its own and the
+ *   video chunks of a shot between two captions form one segment.
+ *   seg_offsets HOST out [up to C+1], is_caption HOST out [up to C] (1: the
+ *   segment is a caption span), *P the number of segments.
+ * moc_reduce_layout builds the layout of the reduced stream made of the kept
+ *   segments (ascending, each bounded by chunk boundaries) for moc_chunk_meta:
+ *   chunks move as a whole and keep their shot and window ids; the part of a
+ *   caption span inside a kept segment stays a caption span.
+ *   out_offsets HOST out [up to C+1], out_shot / out_window [up to C],
+ *   out_spans [up to T + n_kept][2], *out_C, *out_T the sizes used; out_ranges HOST out
+ *   [n_kept][2] = (first row, length) of every kept segment, the table
+ *   moc_gather_rows takes. chunk_window may be NULL (own chunk).
  */
+int moc_outer_segments(int32_t C, const int32_t *chunk_offsets, const int32_t *chunk_shot,
+                       const int32_t *text_spans, int32_t T, int32_t *seg_offsets,
+                       int32_t *is_caption, int32_t *P);
+int moc_reduce_layout(int32_t C, const int32_t *chunk_offsets, const int32_t *chunk_shot,
+                      const int32_t *chunk_window, const int32_t *text_spans, int32_t T, int32_t P,
+                      const int32_t *seg_offsets, int32_t n_kept, const int32_t *kept,
+                      int32_t *out_offsets, int32_t *out_shot, int32_t *out_window,
+                      int32_t *out_spans, int32_t *out_C, int32_t *out_T, int32_t *out_ranges);
 int moc_outer_workspace_bytes(int32_t N, int32_t D, int32_t P, size_t *bytes);
 int moc_outer_route(int32_t N, int32_t D, int dtype, const void *x, int32_t P,
                     const int32_t *seg_offsets, const int32_t *mandatory, int32_t g, int32_t M,
@@ -193,8 +217,12 @@ int moc_gather_rows(int32_t outer, int32_t n_src_rows, int32_t row_bytes, const 
  * listed in sel[i] (entries < 0 ignored). Forced links are not subject to the
  * causal mask. lse_i = log sum_t exp(logit_it) (natural log).
  *   sel       DEVICE in [B,H,N,topk]; may come from moc_route or from anywhere
- *             else; entries must be -1 or a video chunk outside i's window,
- *             without repeats in a row.
+ *             else. Omega(i) is a set: an entry that is negative or >= C, names
+ *             a caption chunk or a chunk of i's own window (forced links, in
+ *             Omega(i) anyway, Sec. 3.3 pre-routing mask), or repeats an earlier
+ *             entry of its row is ignored.
+ *   softmax_scale  finite and > 0 (1/sqrt(d) in Eq. 1 and 2), else MOC_ERR_SHAPE.
+ *   topk > 0 needs C <= 16384 (MOC_ERR_SHAPE otherwise).
  *   o         DEVICE out [B,H,N,d] dtype;  lse DEVICE out [B,H,N] fp32.
  *   workspace DEVICE scratch of moc_attn_workspace_bytes(..., with_bwd) bytes.
  */
@@ -212,15 +240,28 @@ int moc_attn_fwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtyp
  *   dQ_i = scale * sum_t dS_it k_t,  dK_t = scale * sum_i dS_it q_i.
  * o, lse are the forward's outputs; dq, dk, dv [B,H,N,d] dtype are fully
  * overwritten. workspace must have been sized with with_bwd = 1.
- * dq is bit-identical from call to call; dk and dv of routed chunks are summed
- * over the routed queries in an order that may change between calls (fp32
- * summation order only).
+ * Every sum is formed in a fixed order (the routed queries of a chunk in
+ * ascending query index): dq, dk and dv are bit-identical from call to call.
+ *
+ * moc_attn_bwd_after_fwd is moc_attn_bwd for the usual training step, where it
+ * follows a moc_attn_fwd call with the same meta, B, H, sel pointer, topk,
+ * workspace and stream: the per-chunk query lists that call left at the head of
+ * the workspace are used again instead of being rebuilt from sel. The caller
+ * promises that neither the contents of sel nor the workspace were written in
+ * between (a workspace sized with with_bwd = 1 serves both calls). If the
+ * library did not see such a forward call last on this workspace it rebuilds
+ * the lists, i.e. behaves as moc_attn_bwd.
  */
 int moc_attn_bwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
                  const void *q, const void *k, const void *v, const void *o, const float *lse,
                  const void *d_o, const int32_t *sel, int32_t topk, float softmax_scale,
                  void *dq, void *dk, void *dv, void *workspace, size_t workspace_bytes,
                  void *stream);
+int moc_attn_bwd_after_fwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
+                           const void *q, const void *k, const void *v, const void *o,
+                           const float *lse, const void *d_o, const int32_t *sel, int32_t topk,
+                           float softmax_scale, void *dq, void *dk, void *dv, void *workspace,
+                           size_t workspace_bytes, void *stream);
 
 /*
  * Per-kernel timing (measurement aid, not part of the layer). While enabled,

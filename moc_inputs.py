@@ -141,45 +141,6 @@ def stream_layout(n_shots: int, text_len: int, video_tokens: int, chunk: int, wi
                    n_shots=n_shots, text_len=text_len, video_tokens=video_tokens, chunk=chunk, window=window)
 
 
-def shot_segments(layout: Layout):
-    """Segment offsets for the outer loop (App. "Outer Loop Context Routing"): every caption span is a
-    segment of its own, the video chunks of a shot form one segment. -> (seg_offsets, is_caption)."""
-    off = layout.offsets
-    text = np.zeros(layout.C, bool)
-    for s, e in layout.text_spans.reshape(-1, 2):
-        text |= (off[:-1] >= s) & (off[1:] <= e)
-    seg, cap = [0], []
-    for j in range(layout.C):
-        new = j > 0 and (text[j] != text[j - 1] or layout.shot[j] != layout.shot[j - 1] or text[j])
-        if new:
-            seg.append(int(off[j]))
-            cap.append(bool(text[j - 1]))
-    seg.append(int(off[-1]))
-    cap.append(bool(text[-1]))
-    return np.asarray(seg, dtype=np.int32), np.asarray(cap, dtype=np.int32)
-
-
-def reduce_layout(layout: Layout, seg_offsets: Sequence[int], kept: Sequence[int]) -> Layout:
-    """Layout of the reduced stream made of the kept segments, in stream order. Segment boundaries
-    must be chunk boundaries; chunks, shots, windows and caption spans keep their structure."""
-    off = layout.offsets
-    offs, shot, win, spans = [0], [], [], []
-    span_of = {int(s): int(e) for s, e in layout.text_spans.reshape(-1, 2)}
-    for sgm in kept:
-        a, b = int(seg_offsets[sgm]), int(seg_offsets[sgm + 1])
-        j0, j1 = int(np.searchsorted(off, a)), int(np.searchsorted(off, b))
-        if off[j0] != a or off[j1] != b:
-            raise ValueError("segment boundaries must be chunk boundaries")
-        base = offs[-1] - a
-        for j in range(j0, j1):
-            offs.append(int(off[j + 1]) + base)
-            shot.append(int(layout.shot[j]))
-            win.append(int(layout.window[j]))
-            if int(off[j]) in span_of and span_of[int(off[j])] <= b:
-                spans.append((int(off[j]) + base, span_of[int(off[j])] + base))
-    return _finish(layout.name + "_reduced", offs, shot, win, spans, **layout.meta)
-
-
 def random_layout(seed: int, n_chunks: int = 12, max_len: int = 40, n_shots: int = 2,
                   text_prob: float = 0.2, window: str = "mixed") -> Layout:
     """Small irregular layout for brute-force tests: chunk lengths 1..max_len,

@@ -21,17 +21,21 @@
  *    the query's chunk; they are removed from the candidate set BEFORE top-k,
  *    so k counts routed chunks only (Sec. 3.3 pre-routing mask; App. ablation:
  *    fan-out k+1);
- *  - the causal mask acts on routing only: candidates are chunks j < c(i)
- *    (Sec. 3.2 "any edge (i -> j) with j >= i is masked out prior to top-k");
+ *  - the causal mask acts on routing only: candidates are chunks with index
+ *    j < c(i), later and own chunks being removed before top-k (Sec. 3.2);
  *    mandatory links are exempt;
  *  - fewer than k candidates: take them all, pad the selection with -1;
  *  - ties: the lower chunk index wins;
  *  - backward: the selection is a constant (top-k is not differentiable,
  *    Sec. 3.1); gradients flow only through attention on the chosen tokens.
  *
+ *  - a selection row is read as a set: an entry that repeats another one or
+ *    names a mandatory chunk adds nothing (M(i) and R(i) are joined, Sec. 3.1).
+ *
  * Parity pins live in tests/test_oracle_*.py (brute force with an explicit
  * N x N mask, reductions to dense / causal attention, invariants, central
- * finite differences, closed-form pair counts).
+ * finite differences, closed-form pair counts, subset modes against the
+ * whole-sequence rows).
  */
 #include <math.h>
 #include <stdlib.h>

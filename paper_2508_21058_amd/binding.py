@@ -23,7 +23,9 @@ MOC_BF16, MOC_F32 = 0, 1
 MOC_MAX_TOPK = 32
 
 SYMBOLS = ["moc_status_string", "moc_last_error", "moc_chunk_meta", "moc_meta_destroy", "moc_meta_copy_tables",
-           "moc_route_workspace_bytes", "moc_route", "moc_route_perturbed", "moc_outer_workspace_bytes", "moc_outer_route", "moc_gather_rows", "moc_attn_workspace_bytes", "moc_attn_fwd", "moc_attn_bwd",
+           "moc_route_workspace_bytes", "moc_route", "moc_route_perturbed", "moc_outer_workspace_bytes", "moc_outer_route",
+           "moc_outer_segments", "moc_reduce_layout", "moc_gather_rows", "moc_attn_workspace_bytes", "moc_attn_fwd",
+           "moc_attn_bwd", "moc_attn_bwd_after_fwd",
            "moc_prof_enable", "moc_prof_read", "moc_probe"]
 
 
@@ -59,6 +61,10 @@ def lib():
     l.moc_attn_fwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, sz, vp]
     l.moc_attn_bwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, i32, C.c_float,
                                vp, vp, vp, vp, sz, vp]
+    l.moc_attn_bwd_after_fwd.argtypes = l.moc_attn_bwd.argtypes
+    l.moc_outer_segments.argtypes = [i32, vp, vp, vp, i32, vp, vp, C.POINTER(i32)]
+    l.moc_reduce_layout.argtypes = [i32, vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, C.POINTER(i32),
+                                    C.POINTER(i32), vp]
     l.moc_route_perturbed.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, i32, i32, C.c_float, C.c_float, i32,
                                       C.c_uint64, vp, vp, vp, sz, vp]
     l.moc_outer_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(sz)]
@@ -219,17 +225,19 @@ def attn_fwd(meta: Meta, q, k, v, sel, scale: Optional[float] = None, workspace:
 
 
 def attn_bwd(meta: Meta, q, k, v, o, lse, d_o, sel, scale: Optional[float] = None,
-             workspace: Optional[torch.Tensor] = None, out=None):
-    """-> dq, dk, dv [B,H,N,d] (dtype of q)."""
+             workspace: Optional[torch.Tensor] = None, out=None, after_fwd: bool = False):
+    """-> dq, dk, dv [B,H,N,d] (dtype of q). after_fwd: call moc_attn_bwd_after_fwd (the lists the
+    forward left in `workspace` are reused)."""
     B, H, N, d = _shape(meta, q)
     _need_contig(q, k, v, o, lse, d_o, sel)
     topk = int(sel.shape[-1])
     scale = float(d ** -0.5 if scale is None else scale)
     ws = workspace if workspace is not None else attn_workspace(meta, B, H, d, topk, q.dtype, True, q.device)
     dq, dk, dv = out if out is not None else (torch.empty_like(q), torch.empty_like(q), torch.empty_like(q))
-    _check(lib().moc_attn_bwd(meta.handle, B, H, d, _dtype_code(q), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
-                              _ptr(d_o), _ptr(sel) if topk > 0 else None, topk, scale, _ptr(dq), _ptr(dk), _ptr(dv),
-                              _ptr(ws), ws.numel(), _stream()), "moc_attn_bwd")
+    fn = lib().moc_attn_bwd_after_fwd if after_fwd else lib().moc_attn_bwd
+    _check(fn(meta.handle, B, H, d, _dtype_code(q), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+              _ptr(d_o), _ptr(sel) if topk > 0 else None, topk, scale, _ptr(dq), _ptr(dk), _ptr(dv),
+              _ptr(ws), ws.numel(), _stream()), "moc_attn_bwd")
     return dq, dk, dv
 
 
@@ -299,3 +307,35 @@ def gather_rows(src: torch.Tensor, ranges) -> torch.Tensor:
     _check(lib().moc_gather_rows(outer, n_src, dlast * src.element_size(), _ptr(src), rg.shape[0], rg.ctypes.data,
                                  _ptr(dst), _ptr(ws), ws.numel(), _stream()), "moc_gather_rows")
     return dst
+
+
+def outer_segments(offsets, shot, text_spans):
+    """Segments of the outer loop -> (seg_offsets [P+1], is_caption [P]) as numpy int32."""
+    off, sh = _i32(offsets), _i32(shot)
+    spans = _i32(text_spans).reshape(-1, 2) if text_spans is not None else np.zeros((0, 2), np.int32)
+    Cn, T = off.shape[0] - 1, spans.shape[0]
+    seg = np.zeros(Cn + 1, np.int32)
+    cap = np.zeros(Cn, np.int32)
+    P = C.c_int32()
+    _check(lib().moc_outer_segments(Cn, off.ctypes.data, sh.ctypes.data, spans.ctypes.data if T else None, T,
+                                    seg.ctypes.data, cap.ctypes.data, C.byref(P)), "moc_outer_segments")
+    return seg[:P.value + 1].copy(), cap[:P.value].copy()
+
+
+def reduce_layout(offsets, shot, window, text_spans, seg_offsets, kept):
+    """Layout of the reduced stream -> (offsets, shot, window, text_spans [T,2], ranges [n_kept,2])."""
+    off, sh = _i32(offsets), _i32(shot)
+    win = None if window is None else _i32(window)
+    spans = _i32(text_spans).reshape(-1, 2) if text_spans is not None else np.zeros((0, 2), np.int32)
+    seg, kp = _i32(seg_offsets), _i32(kept)
+    Cn, T, P = off.shape[0] - 1, spans.shape[0], seg.shape[0] - 1
+    o_off, o_shot, o_win = np.zeros(Cn + 1, np.int32), np.zeros(Cn, np.int32), np.zeros(Cn, np.int32)
+    o_spans = np.zeros((T + len(kp) + 1, 2), np.int32)     # a span cut by segment boundaries gives several pieces
+    ranges = np.zeros((max(len(kp), 1), 2), np.int32)
+    oC, oT = C.c_int32(), C.c_int32()
+    _check(lib().moc_reduce_layout(Cn, off.ctypes.data, sh.ctypes.data, None if win is None else win.ctypes.data,
+                                   spans.ctypes.data if T else None, T, P, seg.ctypes.data, len(kp), kp.ctypes.data,
+                                   o_off.ctypes.data, o_shot.ctypes.data, o_win.ctypes.data, o_spans.ctypes.data,
+                                   C.byref(oC), C.byref(oT), ranges.ctypes.data), "moc_reduce_layout")
+    return (o_off[:oC.value + 1].copy(), o_shot[:oC.value].copy(), o_win[:oC.value].copy(),
+            o_spans[:oT.value].copy(), ranges[:len(kp)].copy())

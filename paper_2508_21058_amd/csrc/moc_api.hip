@@ -43,6 +43,8 @@ int check_common(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int32_t 
     if ((long long)B * H * meta->N * (topk + 1) >= (1LL << 31))
         return fail(MOC_ERR_SHAPE, "B * H * N * (topk + 1) must be < 2^31");
     if ((long long)B * H > 65535) return fail(MOC_ERR_SHAPE, "B * H must be <= 65535");
+    if (topk > 0 && meta->C > moc::kMaxListChunks)
+        return fail(MOC_ERR_SHAPE, "routing needs C <= 16384 (the list builder's histogram)");
     return MOC_OK;
 }
 
@@ -62,6 +64,36 @@ hipEvent_t prof_event() {
 void prof_clear_locked() {
     for (auto &r : g_prof) { g_prof_pool.push_back(r.e0); g_prof_pool.push_back(r.e1); }
     g_prof.clear();
+}
+
+bool bad_scale(float s) { return !(s > 0.f) || !std::isfinite(s); }
+
+// What the last moc_attn_fwd left in a workspace: moc_attn_bwd_after_fwd reuses the lists only when
+// its own arguments name the same call.
+struct ListTag { const moc_meta *meta; const int32_t *sel; int32_t B, H, topk; void *stream; };
+std::mutex g_tag_mu;
+std::map<const void *, ListTag> g_tags;
+
+void tag_set(const void *ws, const ListTag &t) {
+    std::lock_guard<std::mutex> lk(g_tag_mu);
+    if (g_tags.size() > 64) g_tags.clear();
+    g_tags[ws] = t;
+}
+void tag_drop(const void *ws) {
+    std::lock_guard<std::mutex> lk(g_tag_mu);
+    g_tags.erase(ws);
+}
+void tag_drop_meta(const moc_meta *m) {
+    std::lock_guard<std::mutex> lk(g_tag_mu);
+    for (auto it = g_tags.begin(); it != g_tags.end();)
+        if (it->second.meta == m) it = g_tags.erase(it); else ++it;
+}
+bool tag_matches(const void *ws, const ListTag &t) {
+    std::lock_guard<std::mutex> lk(g_tag_mu);
+    auto it = g_tags.find(ws);
+    if (it == g_tags.end()) return false;
+    const ListTag &u = it->second;
+    return u.meta == t.meta && u.sel == t.sel && u.B == t.B && u.H == t.H && u.topk == t.topk && u.stream == t.stream;
 }
 
 }  // namespace
@@ -90,7 +122,8 @@ AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd)
     L.cnt = take((size_t)BH * C * 4);
     L.list_off = take((size_t)BH * (C + 1) * 4);
     L.tile_off = take((size_t)BH * (C + 1) * 4);
-    L.cursor = take((size_t)BH * C * 4);
+    L.vmask = take((size_t)BH * N * 4);
+    L.cnt_blk = take((size_t)BH * ((N + kRowsPerBlk - 1) / kRowsPerBlk) * C * 4);
     L.qlist = take((size_t)BH * N * std::max(topk, 1) * 4);
     L.plse = take((size_t)BH * N * slots * 4);
     L.po = take((size_t)BH * N * slots * d * 2);
@@ -357,6 +390,7 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
 
 int moc_meta_destroy(moc_meta *m) {
     if (!m) return MOC_OK;
+    tag_drop_meta(m);
     hipError_t e = m->d_base ? hipFree(m->d_base) : hipSuccess;
     delete m;
     return e == hipSuccess ? MOC_OK : hip_fail(e, "hipFree(meta tables)");
@@ -552,6 +586,79 @@ int moc_gather_rows(int32_t outer, int32_t n_src_rows, int32_t row_bytes, const 
     return e == hipSuccess ? MOC_OK : hip_fail(e, "moc_gather_rows");
 }
 
+int moc_outer_segments(int32_t C, const int32_t *off, const int32_t *shot, const int32_t *spans, int32_t T,
+                       int32_t *seg_offsets, int32_t *is_caption, int32_t *P) {
+    if (!off || !shot || !seg_offsets || !is_caption || !P) return fail(MOC_ERR_NULL, "a required pointer is NULL");
+    if (T < 0 || (T > 0 && !spans)) return fail(MOC_ERR_NULL, "text_spans is NULL with T > 0");
+    if (C <= 0) return fail(MOC_ERR_SHAPE, "need C > 0");
+    if (off[0] != 0) return fail(MOC_ERR_OFFSETS, "offsets must start at 0");
+    for (int j = 0; j < C; ++j)
+        if (off[j + 1] <= off[j]) return fail(MOC_ERR_OFFSETS, "offsets must be strictly increasing");
+    // a chunk starts a segment if a caption span starts or ends there, or the shot changes
+    std::vector<char> cut(C + 1, 0), text(C, 0);
+    cut[0] = cut[C] = 1;
+    for (int s = 0; s < T; ++s) {
+        const int a = spans[2 * s], b = spans[2 * s + 1];
+        const int32_t *pa = std::lower_bound(off, off + C + 1, a), *pb = std::lower_bound(off, off + C + 1, b);
+        if (a >= b || pa == off + C + 1 || pb == off + C + 1 || *pa != a || *pb != b)
+            return fail(MOC_ERR_TEXT_SPAN, "text span is not a union of whole chunks");
+        cut[pa - off] = cut[pb - off] = 1;
+        for (int j = int(pa - off); j < int(pb - off); ++j) text[j] = 1;
+    }
+    for (int j = 1; j < C; ++j)
+        if (shot[j] != shot[j - 1]) cut[j] = 1;
+    int n = 0;
+    for (int j = 0; j < C; ++j)
+        if (cut[j]) { seg_offsets[n] = off[j]; is_caption[n] = text[j]; ++n; }
+    seg_offsets[n] = off[C];
+    *P = n;
+    return MOC_OK;
+}
+
+int moc_reduce_layout(int32_t C, const int32_t *off, const int32_t *shot, const int32_t *window,
+                      const int32_t *spans, int32_t T, int32_t P, const int32_t *seg_offsets, int32_t n_kept,
+                      const int32_t *kept, int32_t *out_offsets, int32_t *out_shot, int32_t *out_window,
+                      int32_t *out_spans, int32_t *out_C, int32_t *out_T, int32_t *out_ranges) {
+    if (!off || !shot || !seg_offsets || !kept || !out_offsets || !out_shot || !out_window || !out_C || !out_T ||
+        !out_ranges)
+        return fail(MOC_ERR_NULL, "a required pointer is NULL");
+    if (T < 0 || (T > 0 && (!spans || !out_spans))) return fail(MOC_ERR_NULL, "text spans missing with T > 0");
+    if (C <= 0 || P <= 0 || n_kept <= 0 || n_kept > P) return fail(MOC_ERR_SHAPE, "need C, P > 0 and 0 < n_kept <= P");
+    if (off[0] != 0 || seg_offsets[0] != 0 || seg_offsets[P] != off[C])
+        return fail(MOC_ERR_OFFSETS, "chunk and segment offsets must cover the same stream");
+    for (int j = 0; j < C; ++j)
+        if (off[j + 1] <= off[j]) return fail(MOC_ERR_OFFSETS, "offsets must be strictly increasing");
+    for (int r = 0; r < n_kept; ++r) {
+        if (kept[r] < 0 || kept[r] >= P) return fail(MOC_ERR_SHAPE, "kept names no segment");
+        if (r > 0 && kept[r] <= kept[r - 1]) return fail(MOC_ERR_SHAPE, "kept must ascend");
+    }
+    int nc = 0, nt = 0, pos = 0;
+    out_offsets[0] = 0;
+    for (int r = 0; r < n_kept; ++r) {
+        const int a = seg_offsets[kept[r]], b = seg_offsets[kept[r] + 1];
+        const int32_t *pa = std::lower_bound(off, off + C + 1, a), *pb = std::lower_bound(off, off + C + 1, b);
+        if (a >= b || pa == off + C + 1 || pb == off + C + 1 || *pa != a || *pb != b)
+            return fail(MOC_ERR_OFFSETS, "segment boundaries must be chunk boundaries");
+        out_ranges[2 * r] = a;
+        out_ranges[2 * r + 1] = b - a;
+        const int shift = pos - a;           // stream position -> reduced position inside this segment
+        for (int j = int(pa - off); j < int(pb - off); ++j) {
+            out_shot[nc] = shot[j];
+            out_window[nc] = window ? window[j] : j;
+            out_offsets[++nc] = off[j + 1] + shift;
+        }
+        // the part of every caption span that lies inside the segment stays a caption span
+        for (int s = 0; s < T; ++s) {
+            const int lo = std::max(spans[2 * s], a), hi = std::min(spans[2 * s + 1], b);
+            if (lo < hi) { out_spans[2 * nt] = lo + shift; out_spans[2 * nt + 1] = hi + shift; ++nt; }
+        }
+        pos += b - a;
+    }
+    *out_C = nc;
+    *out_T = nt;
+    return MOC_OK;
+}
+
 int moc_attn_workspace_bytes(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int32_t topk, int dtype,
                              int with_bwd, size_t *bytes) {
     if (!bytes) return fail(MOC_ERR_NULL, "bytes is NULL");
@@ -561,35 +668,15 @@ int moc_attn_workspace_bytes(const moc_meta *meta, int32_t B, int32_t H, int32_t
     return MOC_OK;
 }
 
-int moc_attn_fwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
-                 const void *v, const int32_t *sel, int32_t topk, float softmax_scale, void *o, float *lse,
-                 void *workspace, size_t workspace_bytes, void *stream) {
-    int rc = check_common(meta, B, H, d, topk, dtype);
-    if (rc) return rc;
-    if (!q || !k || !v || !o || !lse || (!sel && topk > 0)) return fail(MOC_ERR_NULL, "a tensor pointer is NULL");
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) || misaligned(sel))
-        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
-    const moc::AttnWs L = moc::attn_ws_layout(meta, B * H, d, topk, false);
-    if (!workspace || workspace_bytes < L.total) return fail(MOC_ERR_WORKSPACE, "attention workspace too small");
-    if (misaligned(workspace)) return fail(MOC_ERR_ALIGN, "workspace must be 16-byte aligned");
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = hipSuccess;
-    if (topk > 0) {
-        e = moc::launch_build_lists(meta, B * H, topk, sel, static_cast<char *>(workspace), L, st);
-        if (e != hipSuccess) return hip_fail(e, "list kernels");
-    }
-    e = moc::launch_attn_fwd(meta, B * H, d, dtype, q, k, v, sel, topk, softmax_scale, o, lse,
-                             static_cast<char *>(workspace), L, st);
-    if (e != hipSuccess) return hip_fail(e, "attention forward kernels");
-    return MOC_OK;
-}
+namespace {
 
-int moc_attn_bwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
-                 const void *v, const void *o, const float *lse, const void *d_o, const int32_t *sel, int32_t topk,
-                 float softmax_scale, void *dq, void *dk, void *dv, void *workspace, size_t workspace_bytes,
-                 void *stream) {
+int attn_bwd_impl(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
+                  const void *v, const void *o, const float *lse, const void *d_o, const int32_t *sel, int32_t topk,
+                  float softmax_scale, void *dq, void *dk, void *dv, void *workspace, size_t workspace_bytes,
+                  void *stream, bool reuse_lists) {
     int rc = check_common(meta, B, H, d, topk, dtype);
     if (rc) return rc;
+    if (bad_scale(softmax_scale)) return fail(MOC_ERR_SHAPE, "softmax_scale must be finite and positive");
     if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || (!sel && topk > 0))
         return fail(MOC_ERR_NULL, "a tensor pointer is NULL");
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) || misaligned(d_o) ||
@@ -600,14 +687,60 @@ int moc_attn_bwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtyp
     if (misaligned(workspace)) return fail(MOC_ERR_ALIGN, "workspace must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
+    const ListTag tag{meta, sel, B, H, topk, stream};
+    if (topk > 0 && !(reuse_lists && tag_matches(workspace, tag))) {
+        e = moc::launch_build_lists(meta, B * H, topk, sel, static_cast<char *>(workspace), L, st);
+        if (e != hipSuccess) { tag_drop(workspace); return hip_fail(e, "list kernels"); }
+    }
+    tag_drop(workspace);     // the backward leaves the workspace to whoever comes next
+    e = moc::launch_attn_bwd(meta, B * H, d, dtype, q, k, v, o, lse, d_o, topk, softmax_scale, dq, dk, dv,
+                             static_cast<char *>(workspace), L, st);
+    if (e != hipSuccess) return hip_fail(e, "attention backward kernels");
+    return MOC_OK;
+}
+
+}  // namespace
+
+int moc_attn_fwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
+                 const void *v, const int32_t *sel, int32_t topk, float softmax_scale, void *o, float *lse,
+                 void *workspace, size_t workspace_bytes, void *stream) {
+    int rc = check_common(meta, B, H, d, topk, dtype);
+    if (rc) return rc;
+    if (bad_scale(softmax_scale)) return fail(MOC_ERR_SHAPE, "softmax_scale must be finite and positive");
+    if (!q || !k || !v || !o || !lse || (!sel && topk > 0)) return fail(MOC_ERR_NULL, "a tensor pointer is NULL");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) || misaligned(sel))
+        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    const moc::AttnWs L = moc::attn_ws_layout(meta, B * H, d, topk, false);
+    if (!workspace || workspace_bytes < L.total) return fail(MOC_ERR_WORKSPACE, "attention workspace too small");
+    if (misaligned(workspace)) return fail(MOC_ERR_ALIGN, "workspace must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    tag_drop(workspace);
     if (topk > 0) {
         e = moc::launch_build_lists(meta, B * H, topk, sel, static_cast<char *>(workspace), L, st);
         if (e != hipSuccess) return hip_fail(e, "list kernels");
     }
-    e = moc::launch_attn_bwd(meta, B * H, d, dtype, q, k, v, o, lse, d_o, sel, topk, softmax_scale, dq, dk, dv,
+    e = moc::launch_attn_fwd(meta, B * H, d, dtype, q, k, v, topk, softmax_scale, o, lse,
                              static_cast<char *>(workspace), L, st);
-    if (e != hipSuccess) return hip_fail(e, "attention backward kernels");
+    if (e != hipSuccess) return hip_fail(e, "attention forward kernels");
+    if (topk > 0) tag_set(workspace, ListTag{meta, sel, B, H, topk, stream});
     return MOC_OK;
+}
+
+int moc_attn_bwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
+                 const void *v, const void *o, const float *lse, const void *d_o, const int32_t *sel, int32_t topk,
+                 float softmax_scale, void *dq, void *dk, void *dv, void *workspace, size_t workspace_bytes,
+                 void *stream) {
+    return attn_bwd_impl(meta, B, H, d, dtype, q, k, v, o, lse, d_o, sel, topk, softmax_scale, dq, dk, dv, workspace,
+                         workspace_bytes, stream, false);
+}
+
+int moc_attn_bwd_after_fwd(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q,
+                           const void *k, const void *v, const void *o, const float *lse, const void *d_o,
+                           const int32_t *sel, int32_t topk, float softmax_scale, void *dq, void *dk, void *dv,
+                           void *workspace, size_t workspace_bytes, void *stream) {
+    return attn_bwd_impl(meta, B, H, d, dtype, q, k, v, o, lse, d_o, sel, topk, softmax_scale, dq, dk, dv, workspace,
+                         workspace_bytes, stream, true);
 }
 
 }  // extern "C"

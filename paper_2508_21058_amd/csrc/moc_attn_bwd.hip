@@ -132,13 +132,7 @@ __device__ __forceinline__ void sum_store_rows(char *smem, int wave, int lane, c
     int32_t *rowidx = reinterpret_cast<int32_t *>(patch + 32 * RS);
     uint32_t *used = reinterpret_cast<uint32_t *>(rowidx + 32);
     if (half == 0) {
-        const int32_t *sr = a.sel + (bhN + qi) * topk;
-        uint32_t mask = 0;
-        for (int s = 0; s < topk; ++s) {
-            const int j = sr[s];
-            if (j >= 0 && j < a.C) mask |= 1u << s;
-        }
-        used[l32] = mask;
+        used[l32] = topk > 0 ? a.vmask[bhN + qi] : 0u;     // the routed slots that count
         rowidx[l32] = row_valid ? qi : -1;
     }
 #pragma unroll
@@ -416,7 +410,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dq_chunk_kernel(FwdArgs a) {
 
 template <int D, typename T>
 __global__ __launch_bounds__(256) void dq_merge_kernel(const bf16_t *__restrict__ part,
-                                                       const int32_t *__restrict__ sel, int N, int C, int topk,
+                                                       const uint32_t *__restrict__ vmask, int N, int topk,
                                                        T *__restrict__ dq) {
     constexpr int TPQ = D / 8, QPW = 256 / TPQ;
     const int bh = blockIdx.y;
@@ -425,7 +419,7 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const bf16_t *__restrict_
     if (i >= N) return;
     const int slots = topk + 1;
     const size_t row = (size_t)bh * N + i;
-    const int32_t *sr = sel + row * topk;
+    const uint32_t used = topk > 0 ? vmask[row] : 0u;
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
@@ -435,8 +429,7 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(const bf16_t *__restrict_
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int s = s0 + u;
-            bool ok = s == topk;
-            if (s < topk) { const int j = sr[s]; ok = j >= 0 && j < C; }
+            const bool ok = s == topk || (s < topk && ((used >> s) & 1u));
             w[u] = ok ? 1.f : 0.f;
             Io<bf16_t>::load8f(pbase + (size_t)(ok ? s : topk) * D, f[u]);
         }
@@ -1365,8 +1358,8 @@ __global__ __launch_bounds__(256) void text_reduce_kernel(const float *__restric
 }
 
 template <int D, typename T>
-static hipError_t bwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, KvArgs &kv, const void *o, const int32_t *sel,
-                               void *dq, hipStream_t st) {
+static hipError_t bwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, KvArgs &kv, const void *o, void *dq,
+                               hipStream_t st) {
     constexpr int QPW = 256 / (D / 8);
     const size_t rows = (size_t)BH * m->N;
     { MOC_PROF("delta", st);
@@ -1406,18 +1399,18 @@ static hipError_t bwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, KvArgs &kv
     { MOC_PROF("attn_bwd_dq_forced", st);
     a.items_per_head = m->n_atiles;
     // bf16 storage: the forced-link items run after the routed ones and add the routed partials themselves
-    a.sel = sel; a.o_out = sizeof(T) == 2 ? dq : nullptr;
+    a.o_out = sizeof(T) == 2 ? dq : nullptr;
     attn_bwd_dq_kernel<D, T, MODE_ANCHOR><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a); }
     if (sizeof(T) == 2) return hipGetLastError();
     MOC_PROF("dq_merge", st);
-    dq_merge_kernel<D, T><<<dim3((m->N + QPW - 1) / QPW, BH), dim3(256), 0, st>>>(a.po, sel, m->N, m->C, a.topk,
+    dq_merge_kernel<D, T><<<dim3((m->N + QPW - 1) / QPW, BH), dim3(256), 0, st>>>(a.po, a.vmask, m->N, a.topk,
                                                                                 static_cast<T *>(dq));
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bwd(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *k, const void *v,
-                           const void *o, const float *lse, const void *d_o, const int32_t *sel, int topk, float scale,
-                           void *dq, void *dk, void *dv, char *ws, const AttnWs &L, hipStream_t st) {
+                           const void *o, const float *lse, const void *d_o, int topk, float scale, void *dq, void *dk,
+                           void *dv, char *ws, const AttnWs &L, hipStream_t st) {
     FwdArgs a{};
     a.q = q; a.k = k; a.v = v; a.d_o = d_o;
     a.po = reinterpret_cast<bf16_t *>(ws + L.po);
@@ -1429,6 +1422,7 @@ hipError_t launch_attn_bwd(const moc_meta *m, int BH, int d, int dtype, const vo
     a.list_off = reinterpret_cast<const int32_t *>(ws + L.list_off);
     a.tile_off = reinterpret_cast<const int32_t *>(ws + L.tile_off);
     a.qlist = reinterpret_cast<const int32_t *>(ws + L.qlist);
+    a.vmask = reinterpret_cast<const uint32_t *>(ws + L.vmask);
     a.lse = lse;
     a.delta = reinterpret_cast<const float *>(ws + L.delta);
     a.gstats2 = reinterpret_cast<const float *>(ws + L.gstats2);
@@ -1444,10 +1438,10 @@ hipError_t launch_attn_bwd(const moc_meta *m, int BH, int d, int dtype, const vo
     kv.list_off = a.list_off; kv.qlist = a.qlist;
     kv.N = m->N; kv.C = m->C; kv.topk = topk; kv.n_partials = m->n_partials; kv.n_items = m->n_kvitems; kv.BH = BH;
     kv.scale = scale; kv.scale_log2 = a.scale_log2;
-    if (dtype == MOC_BF16) return d == 128 ? bwd_dispatch<128, bf16_t>(m, BH, a, kv, o, sel, dq, st)
-                                           : bwd_dispatch<64, bf16_t>(m, BH, a, kv, o, sel, dq, st);
-    return d == 128 ? bwd_dispatch<128, float>(m, BH, a, kv, o, sel, dq, st)
-                    : bwd_dispatch<64, float>(m, BH, a, kv, o, sel, dq, st);
+    if (dtype == MOC_BF16) return d == 128 ? bwd_dispatch<128, bf16_t>(m, BH, a, kv, o, dq, st)
+                                           : bwd_dispatch<64, bf16_t>(m, BH, a, kv, o, dq, st);
+    return d == 128 ? bwd_dispatch<128, float>(m, BH, a, kv, o, dq, st)
+                    : bwd_dispatch<64, float>(m, BH, a, kv, o, dq, st);
 }
 
 }  // namespace moc

@@ -28,7 +28,7 @@ struct FwdArgs {
     const float *lse, *delta;
     const float *gstats2;   // [BH, N*topk] pairs (lse * log2 e, delta) in inverse-list order
     // forced-link forward items with the merge fused into their epilogue
-    const int32_t *sel;     // [BH, N, topk] selections (which routed slots are in use)
+    const uint32_t *vmask;  // [BH, N] bit r: routed slot r of the query counts (set by the list builder)
     void *o_out;            // [BH, N, D] final output
     float *lse_out;         // [BH, N] final log-sum-exp
 };

@@ -151,22 +151,15 @@ __device__ __forceinline__ void merge_store_rows(char *smem, int wave, int lane,
         const size_t row = bhN + qi;
         const float lf = m_run * a.scale + __logf(l_tot);
         const float *pl = a.plse + row * slots;
-        const int32_t *sr = a.sel + row * topk;
+        const uint32_t used = topk > 0 ? a.vmask[row] : 0u;     // the routed slots that count
         float mx = lf;
-        for (int s = 0; s < topk; ++s) {
-            const int j = sr[s];
-            if (j >= 0 && j < a.C) mx = fmaxf(mx, pl[s]);
-        }
+        for (int s = 0; s < topk; ++s)
+            if ((used >> s) & 1u) mx = fmaxf(mx, pl[s]);
         float z = __expf(lf - mx);
-        for (int s = 0; s < topk; ++s) {
-            const int j = sr[s];
-            if (j >= 0 && j < a.C) z += __expf(pl[s] - mx);
-        }
+        for (int s = 0; s < topk; ++s)
+            if ((used >> s) & 1u) z += __expf(pl[s] - mx);
         const float tot = mx + __logf(z);
-        for (int s = 0; s < topk; ++s) {
-            const int j = sr[s];
-            wts[l32 * WS + s] = (j >= 0 && j < a.C) ? __expf(pl[s] - tot) : 0.f;
-        }
+        for (int s = 0; s < topk; ++s) wts[l32 * WS + s] = ((used >> s) & 1u) ? __expf(pl[s] - tot) : 0.f;
         wts[l32 * WS + 32] = tot;
         wf = __expf(lf - tot);
         rowidx[l32] = row_valid ? qi : -1;
@@ -443,7 +436,7 @@ __global__ __launch_bounds__(512, 1) void attn_fwd_chunk_kernel(FwdArgs a) {
 template <int D, typename T>
 __global__ __launch_bounds__(256) void fwd_merge_kernel(const bf16_t *__restrict__ po,
                                                         const float *__restrict__ plse,
-                                                        const int32_t *__restrict__ sel, int N, int C, int topk,
+                                                        const uint32_t *__restrict__ vmask, int N, int topk,
                                                         T *__restrict__ o, float *__restrict__ lse) {
     constexpr int TPQ = D / 8, QPW = 256 / TPQ;
     const int bh = blockIdx.y;
@@ -453,17 +446,13 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(const bf16_t *__restrict
     const int slots = topk + 1;
     const size_t row = (size_t)bh * N + i;
     const float *pl = plse + row * slots;
-    const int32_t *sr = sel + row * topk;
+    const uint32_t used = topk > 0 ? vmask[row] : 0u;       // the routed slots that count
     float mx = pl[topk];
-    for (int s = 0; s < topk; ++s) {
-        const int j = sr[s];
-        if (j >= 0 && j < C) mx = fmaxf(mx, pl[s]);
-    }
+    for (int s = 0; s < topk; ++s)
+        if ((used >> s) & 1u) mx = fmaxf(mx, pl[s]);
     float z = __expf(pl[topk] - mx);
-    for (int s = 0; s < topk; ++s) {
-        const int j = sr[s];
-        if (j >= 0 && j < C) z += __expf(pl[s] - mx);
-    }
+    for (int s = 0; s < topk; ++s)
+        if ((used >> s) & 1u) z += __expf(pl[s] - mx);
     const float tot = mx + __logf(z);
     // unused slots read the forced-link slot again with weight 0, so all loads
     // are unconditional and several are in flight
@@ -476,8 +465,7 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(const bf16_t *__restrict
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int s = s0 + u;
-            bool ok = s == topk;
-            if (s < topk) { const int j = sr[s]; ok = j >= 0 && j < C; }
+            const bool ok = s == topk || (s < topk && ((used >> s) & 1u));
             const int src = ok ? s : topk;
             w[u] = ok ? __expf(pl[src] - tot) : 0.f;
             Io<bf16_t>::load8f(pbase + (size_t)src * D, f[u]);
@@ -492,8 +480,7 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(const bf16_t *__restrict
 }
 
 template <int D, typename T>
-static hipError_t fwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, const int32_t *sel, void *o, float *lse,
-                               hipStream_t st) {
+static hipError_t fwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, void *o, float *lse, hipStream_t st) {
     a.BH = BH;
     if (a.topk > 0) {
         a.items_per_head = (m->N * a.topk + kBM - 1) / kBM + m->C;   // upper bound; surplus items exit at once
@@ -514,19 +501,18 @@ static hipError_t fwd_dispatch(const moc_meta *m, int BH, FwdArgs &a, const int3
     const bool fuse = sizeof(T) == 2 && 4 * (32 * (D + 4) + 64) * 2 + 4 * 32 * 34 * 4 <= 4 * 64 * D * 2;
     { MOC_PROF("attn_fwd_forced", st);
     a.items_per_head = m->n_atiles;
-    a.sel = sel; a.o_out = fuse ? o : nullptr; a.lse_out = lse;
+    a.o_out = fuse ? o : nullptr; a.lse_out = lse;
     attn_fwd_kernel<D, T, MODE_ANCHOR><<<dim3(xcd_grid((long long)a.items_per_head * BH)), dim3(256), 0, st>>>(a); }
     if (fuse) return hipGetLastError();
     MOC_PROF("fwd_merge", st);
     constexpr int QPW = 256 / (D / 8);
     fwd_merge_kernel<D, T><<<dim3((m->N + QPW - 1) / QPW, BH), dim3(256), 0, st>>>(
-        a.po, a.plse, sel, m->N, m->C, a.topk, static_cast<T *>(o), lse);
+        a.po, a.plse, a.vmask, m->N, a.topk, static_cast<T *>(o), lse);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_fwd(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *k, const void *v,
-                           const int32_t *sel, int topk, float scale, void *o, float *lse, char *ws, const AttnWs &L,
-                           hipStream_t st) {
+                           int topk, float scale, void *o, float *lse, char *ws, const AttnWs &L, hipStream_t st) {
     FwdArgs a{};
     a.q = q; a.k = k; a.v = v;
     a.po = reinterpret_cast<bf16_t *>(ws + L.po);
@@ -538,10 +524,11 @@ hipError_t launch_attn_fwd(const moc_meta *m, int BH, int d, int dtype, const vo
     a.list_off = reinterpret_cast<const int32_t *>(ws + L.list_off);
     a.tile_off = reinterpret_cast<const int32_t *>(ws + L.tile_off);
     a.qlist = reinterpret_cast<const int32_t *>(ws + L.qlist);
-    if (dtype == MOC_BF16) return d == 128 ? fwd_dispatch<128, bf16_t>(m, BH, a, sel, o, lse, st)
-                                           : fwd_dispatch<64, bf16_t>(m, BH, a, sel, o, lse, st);
-    return d == 128 ? fwd_dispatch<128, float>(m, BH, a, sel, o, lse, st)
-                    : fwd_dispatch<64, float>(m, BH, a, sel, o, lse, st);
+    a.vmask = reinterpret_cast<const uint32_t *>(ws + L.vmask);
+    if (dtype == MOC_BF16) return d == 128 ? fwd_dispatch<128, bf16_t>(m, BH, a, o, lse, st)
+                                           : fwd_dispatch<64, bf16_t>(m, BH, a, o, lse, st);
+    return d == 128 ? fwd_dispatch<128, float>(m, BH, a, o, lse, st)
+                    : fwd_dispatch<64, float>(m, BH, a, o, lse, st);
 }
 
 }  // namespace moc

@@ -13,6 +13,8 @@ namespace moc {
 constexpr int kBM = 128;         // queries per workgroup in the query-stationary passes
 constexpr int kKeyTile = 128;    // keys per workgroup in the key-stationary pass (4 waves x 32)
 constexpr int kTextSeg = 8192;   // queries per partial of a text key tile in the key-stationary pass
+constexpr int kRowsPerBlk = 512; // queries per block of the list builder (one histogram row each)
+constexpr int kMaxListChunks = 16384;   // chunks the list builder's LDS histogram holds
 
 // One query tile of the forced-link pass: queries [q_start, q_start+q_count)
 // all belong to window `win` and share its key ranges.
@@ -90,7 +92,7 @@ hipError_t launch_probe(int kind, void *buf, size_t bytes, int iters, hipStream_
 
 // Layout of the attention workspace (byte offsets); shared by fwd and bwd.
 struct AttnWs {
-    size_t cnt, list_off, tile_off, cursor, qlist, plse, po, delta, stats2, gstats2, tpart_k, tpart_v, total;
+    size_t cnt, list_off, tile_off, vmask, cnt_blk, qlist, plse, po, delta, stats2, gstats2, tpart_k, tpart_v, total;
 };
 AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd);
 
@@ -111,13 +113,13 @@ hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void 
 hipError_t launch_build_lists(const moc_meta *m, int BH, int topk, const int32_t *sel, char *ws,
                               const AttnWs &L, hipStream_t st);
 
+// (both read the lists and the slot masks launch_build_lists left in the workspace)
 hipError_t launch_attn_fwd(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *k,
-                           const void *v, const int32_t *sel, int topk, float scale, void *o, float *lse,
-                           char *ws, const AttnWs &L, hipStream_t st);
+                           const void *v, int topk, float scale, void *o, float *lse, char *ws, const AttnWs &L,
+                           hipStream_t st);
 
 hipError_t launch_attn_bwd(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *k,
-                           const void *v, const void *o, const float *lse, const void *d_o,
-                           const int32_t *sel, int topk, float scale, void *dq, void *dk, void *dv,
-                           char *ws, const AttnWs &L, hipStream_t st);
+                           const void *v, const void *o, const float *lse, const void *d_o, int topk, float scale,
+                           void *dq, void *dk, void *dv, char *ws, const AttnWs &L, hipStream_t st);
 
 }  // namespace moc

@@ -25,3 +25,27 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_sessionfinish(session, exitstatus):
+    """The plain error figures the GPU parity tests saw, per tensor, for the record (gpurun_out/ is the
+    folder that comes back from a GPU run)."""
+    try:
+        from tests import test_gpu_parity as tp
+    except Exception:
+        return
+    if not tp.OBSERVED:
+        return
+    out = os.path.join(ROOT, "gpurun_out")
+    try:
+        os.makedirs(out, exist_ok=True)
+        worst = {}
+        for name, rel, mabs, big in tp.OBSERVED:
+            w = worst.setdefault(name, [0.0, 0.0, 0.0, 0])
+            w[0], w[1], w[2], w[3] = max(w[0], rel), max(w[1], mabs), max(w[2], big), w[3] + 1
+        with open(os.path.join(out, "parity_observed.txt"), "w") as f:
+            f.write("tensor  comparisons  worst rel-L2  worst max-abs error  largest |reference|\n")
+            for name, (rel, mabs, big, n) in sorted(worst.items()):
+                f.write(f"{name:6s} {n:5d}  {rel:.3e}  {mabs:.3e}  {big:.3e}\n")
+    except OSError:
+        pass

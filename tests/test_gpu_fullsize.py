@@ -5,8 +5,9 @@ outputs the oracle can compute one by one:
   - pooled keys of one head, all chunks;
   - selections of one head, all N queries (tie tolerance as in the small tests);
   - o, lse, dq at sampled queries of that head;
-  - dk, dv at all tokens of sampled chunks of that head (for the single-shot
-    config also the caption chunk, whose keys are attended by all N queries).
+  - dk, dv at all tokens of sampled chunks of that head; for the single-shot,
+    both eight-shot and one sweep case also a caption chunk, whose keys are
+    attended by all N queries (then o and lse are compared on the whole head).
 
 The head checked has the oracle's selection injected before the attention
 calls, so no tie can leak into the attention comparison.
@@ -48,20 +49,18 @@ def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=Non
     # stage c: selections of the whole head
     sel_ref, _ = mo.route(L, qn, kbar, topk, causal)
     sel_gpu = sel[0, head].cpu().numpy()
-    bad = np.nonzero((np.sort(sel_gpu, -1) != np.sort(sel_ref[0, 0], -1)).any(-1))[0].astype(np.int32)
+    # every row that differs anywhere (set or order) must be explained by ties in the oracle's scores
+    bad = np.nonzero((sel_gpu != sel_ref[0, 0]).any(-1))[0].astype(np.int32)
     if len(bad):
         assert len(bad) <= max(2, N // 2000), f"{len(bad)} rows differ"
         _, sc, _ = mo.route(L, qn, kbar, topk, causal, bad, want_scores=True)
         check_sel(sel_gpu[bad], sel_ref[0, 0][bad], sc[0, 0], topk)
-    # order inside rows (best first) where the sets agree
-    same = np.setdiff1d(np.arange(N), bad)
-    assert (sel_gpu[same] == sel_ref[0, 0][same]).mean() > 0.999
 
     # stage d with the oracle's selection for this head
     sel[0, head] = torch.from_numpy(sel_ref[0, 0]).to("cuda")
     ws = mb.attn_workspace(meta, B, H, d, topk, torch.bfloat16, True)
     o, lse = mb.attn_fwd(meta, q, k, v, sel, None, ws)
-    dq, dk, dv = mb.attn_bwd(meta, q, k, v, o, lse, d_o, sel, None, ws)
+    dq, dk, dv = mb.attn_bwd(meta, q, k, v, o, lse, d_o, sel, None, ws, None, after_fwd=True)    # as bench.py's step
     torch.cuda.synchronize()
 
     rng = np.random.default_rng(5)
@@ -72,7 +71,8 @@ def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=Non
     chunks = np.array(sorted(chunks), dtype=np.int32)
     att = np.zeros(N, bool)
     for j in chunks:
-        att |= (L.kind[j] == 1) | (L.win[L.chunk_of] == L.win[j]) | (sel_ref[0, 0] == j).any(-1)
+        if L.kind[j] == 0:
+            att |= (L.win[L.chunk_of] == L.win[j]) | (sel_ref[0, 0] == j).any(-1)
     extra = rng.choice(N, size=n_sample, replace=False)
     # last queries, first queries, a caption query and random ones are always sampled
     att[extra] = True
@@ -80,14 +80,23 @@ def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=Non
     qidx = np.nonzero(att)[0].astype(np.int32)
 
     sel_s = sel_ref[:, :, qidx]
-    o_ref, lse_ref, _ = mo.attn_fwd(L, qn, kn, vn, sel_s, None, qidx)
-    check_close("o", o[0, head].float().cpu().numpy()[qidx], o_ref[0, 0])
-    check_close("lse", lse[0, head].cpu().numpy()[qidx], lse_ref[0, 0])
+    if with_text_chunk:
+        # a caption chunk is attended by every query: its dK / dV need o and lse of the whole head, so the
+        # forward is compared on all N queries; dQ stays on the sample
+        o_all, lse_all, _ = mo.attn_fwd(L, qn, kn, vn, sel_ref)
+        check_close("o", o[0, head].float().cpu().numpy(), o_all[0, 0])
+        check_close("lse", lse[0, head].cpu().numpy(), lse_all[0, 0])
+        o_ref, lse_ref = o_all[:, :, qidx], lse_all[:, :, qidx]
+        o_full, lse_full = o_all, lse_all
+    else:
+        o_ref, lse_ref, _ = mo.attn_fwd(L, qn, kn, vn, sel_s, None, qidx)
+        check_close("o", o[0, head].float().cpu().numpy()[qidx], o_ref[0, 0])
+        check_close("lse", lse[0, head].cpu().numpy()[qidx], lse_ref[0, 0])
+        o_full = np.zeros((1, 1, N, d)); o_full[0, 0, qidx] = o_ref[0, 0]
+        lse_full = np.zeros((1, 1, N)); lse_full[0, 0, qidx] = lse_ref[0, 0]
     dq_ref = mo.attn_bwd_dq(L, qn, kn, vn, sel_s, o_ref, lse_ref, don[:, :, qidx], None, qidx)
     check_close("dq", dq[0, head].float().cpu().numpy()[qidx], dq_ref[0, 0])
 
-    o_full = np.zeros((1, 1, N, d)); o_full[0, 0, qidx] = o_ref[0, 0]
-    lse_full = np.zeros((1, 1, N)); lse_full[0, 0, qidx] = lse_ref[0, 0]
     dk_ref, dv_ref = mo.attn_bwd_dkdv(L, qn, kn, vn, sel_ref, o_full, lse_full, don, None, chunks)
     rows = np.concatenate([np.arange(L.off[j], L.off[j + 1]) for j in chunks])
     check_close("dk", dk[0, head].float().cpu().numpy()[rows], dk_ref[0, 0][rows])
@@ -102,12 +111,12 @@ def test_single_shot_config_forward_backward():
 
 def test_eight_shot_config_frame_window():
     """Eight-shot configuration (benchmark workload): 8 x (256 + 9 x 1560) tokens, frame window, k=8."""
-    _run("eight", "frame", head=17, n_sample=384, with_text_chunk=False)
+    _run("eight", "frame", head=17, n_sample=384, with_text_chunk=True)
 
 
 def test_eight_shot_config_shot_window():
     """Config 4 with the whole shot as the forced local window (the multi-shot reading)."""
-    _run("eight", "shot", head=2, n_sample=256, with_text_chunk=False)
+    _run("eight", "shot", head=2, n_sample=256, with_text_chunk=True)
 
 
 def test_sweep_config_chunk_130():
@@ -150,4 +159,6 @@ def test_sweep_config_chunk_260_k16():
 
 
 def test_sweep_config_chunk_260_k2():
-    _run("sweep", "frame", head=4, n_sample=128, with_text_chunk=False, chunk=260, topk=2, n_chunks=1)
+    """... and at its narrowest, with a caption chunk among the sampled key chunks: its 256 keys are attended by
+    all 457,472 queries (56 query segments of partial sums and the fixed-order reduction)."""
+    _run("sweep", "frame", head=4, n_sample=128, with_text_chunk=True, chunk=260, topk=2, n_chunks=1)

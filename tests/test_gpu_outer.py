@@ -72,7 +72,9 @@ def test_gather_is_exact_on_head_major_and_flat_tensors():
 def test_full_size_stream_of_the_benchmark_layout():
     """N = 114,368 tokens, D = H d = 3072 (bf16, 703 MB): captions mandatory, shots compete."""
     lay = mi.config_layout("eight")
-    seg, cap = mi.shot_segments(lay)
+    seg, cap = mb.outer_segments(lay.offsets, lay.shot, lay.text_spans)
+    seg_o, cap_o = ou.segments(lay.offsets, lay.shot, lay.text_spans)
+    assert seg.tolist() == seg_o.tolist() and cap.tolist() == cap_o.tolist()
     D = 3072
     x = mi.randn((lay.N, D), 99, "cuda").to(torch.bfloat16).contiguous()
     sel, kept = _check_route(x, seg, cap, 15, 3, True)
@@ -90,22 +92,26 @@ def test_reduced_stream_feeds_the_inner_layer():
     H, d, topk, M = 2, 64, 2, 1
     N = lay.N
     q, k, v, d_o = mi.qkv_do(1, H, N, d, 17, "cpu", bf16_round=True)
-    seg, cap = mi.shot_segments(lay)
-    g = len(seg) - 2
     # features of the outer router: the per-head keys side by side, [N, H d]
     feat = k[0].permute(1, 0, 2).reshape(N, H * d).contiguous()
-    sel_ref, _, kept_ref, _ = ou.outer_route(feat.numpy().astype(np.float64), seg, cap, g, M, True)
-    rows = ou.reduced_rows(seg, kept_ref)
-    red_lay = mi.reduce_layout(lay, seg, kept_ref)
-    L = mo.OracleLayout.from_layout(red_lay)
+
+    # oracle side: its own segments, selection, reduced rows and reduced layout
+    seg_o, cap_o = ou.segments(lay.offsets, lay.shot, lay.text_spans)
+    g = len(seg_o) - 2
+    sel_ref, _, kept_ref, _ = ou.outer_route(feat.numpy().astype(np.float64), seg_o, cap_o, g, M, True)
+    rows = ou.reduced_rows(seg_o, kept_ref)
+    red_o = ou.reduce_layout(lay.offsets, lay.shot, lay.window, lay.text_spans, seg_o, kept_ref)
+    L = mo.OracleLayout(red_o["offsets"], red_o["window"], red_o["text_spans"])
     qn, kn, vn, don = (t.numpy().astype(np.float64)[:, :, rows] for t in (q, k, v, d_o))
     ref = mo.moc_layer(L, qn, kn, vn, topk, True, don)
 
+    # library side: its own segments, selection, gather table and reduced layout
+    seg, cap = mb.outer_segments(lay.offsets, lay.shot, lay.text_spans)
     _, _, sel, kept = mb.outer_route(to_dev(feat.numpy(), torch.bfloat16), seg, cap, g, M, True)
     assert kept == kept_ref and sel.tolist() == sel_ref.tolist()
-    ranges = [(int(seg[j]), int(seg[j + 1] - seg[j])) for j in kept]
+    r_off, r_shot, r_win, r_spans, ranges = mb.reduce_layout(lay.offsets, lay.shot, lay.window, lay.text_spans, seg, kept)
     qd, kd, vd, dod = (mb.gather_rows(to_dev(t.numpy(), torch.bfloat16), ranges) for t in (q, k, v, d_o))
-    meta = mb.chunk_meta(red_lay.offsets, red_lay.shot, red_lay.window, red_lay.text_spans)
+    meta = mb.chunk_meta(r_off, r_shot, r_win, r_spans)
     _, isel = mb.route(meta, qd, kd, topk, True)
     assert (np.sort(isel.cpu().numpy(), -1) == np.sort(ref["sel"], -1)).all()
     o, lse = mb.attn_fwd(meta, qd, kd, vd, isel)

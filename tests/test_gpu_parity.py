@@ -1,10 +1,14 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
 by element, on the same seeded inputs.
 
-Tolerances (bf16 matrix-core path): relative L2 error <= 1e-2 and max abs error
-<= 3e-2 (scaled by max(1, max|ref|), since a bf16 ulp grows with magnitude);
-pooled keys relative error <= 1e-5; selections identical except where the
-oracle's top-k score gap is below 1e-5 of the row's score scale.
+Tolerances (bf16 matrix-core path): relative L2 error <= 1e-2 and, for every
+element, |error| <= 3e-2 * max(1, |reference element|): the stated absolute
+bound of 3e-2 wherever the reference value is at most 1 in magnitude, and the
+same bound relative to the element itself above that (a bf16 result of magnitude
+m carries a rounding step of m * 2^-8). The plain largest absolute error of
+every tensor is printed and collected (see conftest.py).
+Pooled keys: relative error <= 1e-5. Selections: identical, order included,
+except where the oracle's scores tie within 1e-5 of the row's score scale.
 """
 import numpy as np
 import pytest
@@ -17,6 +21,7 @@ from paper_2508_21058_amd import binding as mb
 pytestmark = pytest.mark.gpu
 
 REL_L2, MAX_ABS = 1e-2, 3e-2
+OBSERVED = []          # (test id, tensor, rel l2, max abs error, max |ref|), written out at the end of the session
 
 
 def check_close(name, got, ref):
@@ -24,31 +29,43 @@ def check_close(name, got, ref):
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (name, got.shape, ref.shape)
     assert np.isfinite(got).all(), f"{name}: non-finite values"
+    err = np.abs(got - ref)
     rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
-    mabs = np.abs(got - ref).max()
-    lim = MAX_ABS * max(1.0, np.abs(ref).max())
-    assert rel <= REL_L2 and mabs <= lim, f"{name}: rel_l2={rel:.3e} max_abs={mabs:.3e} (limit {lim:.3e})"
+    mabs = float(err.max()) if err.size else 0.0
+    lim = MAX_ABS * np.maximum(1.0, np.abs(ref))
+    worst = float((err / lim).max()) if err.size else 0.0
+    big = float(np.abs(ref).max()) if ref.size else 0.0
+    OBSERVED.append((name, rel, mabs, big))
+    print(f"[parity] {name}: rel_l2={rel:.3e} max_abs={mabs:.3e} max|ref|={big:.3e} worst/limit={worst:.3f}")
+    assert rel <= REL_L2, f"{name}: rel_l2={rel:.3e}"
+    assert worst <= 1.0, f"{name}: max_abs={mabs:.3e}, an element is off by {worst:.2f}x its limit 3e-2*max(1,|ref|)"
     return rel, mabs
 
 
 def check_sel(sel_gpu, sel_ref, scores, topk):
-    """Rows must hold the same chunk set; a difference is accepted only if every
-    chunk in the symmetric difference scores within 1e-5 * max|s| of the
-    oracle's k-th best. Returns the boolean mask of rows that differ."""
+    """Rows must hold the same chunks in the same order (best first). A difference is accepted only
+    between chunks whose oracle scores tie within tau = 1e-5 * max|s| of the row: a chunk in the
+    symmetric difference must score within tau of the oracle's k-th best, and where the order differs
+    the two chunks at that position must score within tau of each other.
+    Returns the boolean mask of rows whose SET differs."""
     sel_gpu = np.asarray(sel_gpu)
     differ = np.zeros(sel_ref.shape[0], dtype=bool)
-    a = np.sort(sel_gpu, axis=1)
-    b = np.sort(sel_ref, axis=1)
-    for i in np.nonzero((a != b).any(axis=1))[0]:
-        differ[i] = True
-        sg, sr = set(sel_gpu[i]) - {-1}, set(sel_ref[i]) - {-1}
-        assert len(sg) == len(sr), f"row {i}: {sel_gpu[i]} vs {sel_ref[i]}"
+    for i in np.nonzero((sel_gpu != sel_ref).any(axis=1))[0]:
         row = scores[i]
         tau = 1e-5 * np.nanmax(np.abs(row))
-        kth = min(row[j] for j in sr)
-        for j in sg ^ sr:
-            assert np.isfinite(row[j]) and abs(row[j] - kth) <= tau, f"row {i}: chunk {j} not a tie"
-    # order inside a row: best first, except within tolerance
+        sg, sr = set(sel_gpu[i]) - {-1}, set(sel_ref[i]) - {-1}
+        assert len(sg) == len(sr), f"row {i}: {sel_gpu[i]} vs {sel_ref[i]}"
+        if sg != sr:
+            differ[i] = True
+            kth = min(row[j] for j in sr)
+            for j in sg ^ sr:
+                assert np.isfinite(row[j]) and abs(row[j] - kth) <= tau, f"row {i}: chunk {j} not a tie"
+        n = len(sr)
+        assert (sel_gpu[i][n:] == -1).all(), f"row {i}: padding must come last"
+        for p in range(n):
+            a, b = sel_gpu[i][p], sel_ref[i][p]
+            if a != b:
+                assert abs(row[a] - row[b]) <= tau, f"row {i}: position {p} holds {a}, the oracle {b}, no tie"
     return differ
 
 
@@ -102,10 +119,14 @@ def run_case(lay, B, H, d, topk, dtype, seed, causal=True, check_route=True, coh
     check_close("dk", dk.float().cpu().numpy(), ref["dk"])
     check_close("dv", dv.float().cpu().numpy(), ref["dv"])
 
-    # determinism of the forward (no atomics on values): bit-identical rerun
-    o2, lse2 = mb.attn_fwd(meta, qd, kd, vd, sel_ref)
+    # determinism (no atomics anywhere, lists in a fixed order): a rerun is bit-identical; the rerun's
+    # backward takes the lists the forward left in the workspace
+    ws = mb.attn_workspace(meta, B, H, d, topk, dtype, True)
+    o2, lse2 = mb.attn_fwd(meta, qd, kd, vd, sel_ref, None, ws)
+    dq2, dk2, dv2 = mb.attn_bwd(meta, qd, kd, vd, o2, lse2, dod, sel_ref, None, ws, None, after_fwd=True)
     torch.cuda.synchronize()
     assert torch.equal(o, o2) and torch.equal(lse, lse2)
+    assert torch.equal(dq, dq2) and torch.equal(dk, dk2) and torch.equal(dv, dv2)
     meta.close()
     return ref
 
@@ -218,9 +239,8 @@ def test_probes_copy_exactly_and_report_plausible_rates():
 def test_hot_path_replays_from_a_hip_graph():
     """route + forward + backward captured once into a HIP graph (the calls allocate nothing and never
     synchronise) and replayed with fresh inputs, with eager work and synchronisation between the replays.
-    sel, o, lse and dq must equal the eager result bit for bit; dk and dv sum over a chunk's routed queries in
-    the order the list builder's counters handed out, which varies from launch to launch, so they may differ
-    from another run by fp32 summation order (a bf16 rounding step at most)."""
+    Every output must equal the eager result bit for bit (all sums are formed in a fixed order). The backward
+    inside the graph is the variant that reuses the forward's lists."""
     lay = mi.multishot_layout(2, 32, 3, 128, 32, "frame")
     B, H, d, topk, N = 1, 2, 128, 2, lay.N
     meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
@@ -232,7 +252,7 @@ def test_hot_path_replays_from_a_hip_graph():
     def run():
         _, sel = mb.route(meta, stat[0], stat[1], topk, True)
         mb.attn_fwd(meta, stat[0], stat[1], stat[2], sel, None, ws, (o, lse))
-        mb.attn_bwd(meta, stat[0], stat[1], stat[2], o, lse, stat[3], sel, None, ws, grads)
+        mb.attn_bwd(meta, stat[0], stat[1], stat[2], o, lse, stat[3], sel, None, ws, grads, after_fwd=True)
         return sel
 
     def load(seed):
@@ -257,12 +277,7 @@ def test_hot_path_replays_from_a_hip_graph():
         sel_e = run()                                          # eager, same inputs
         torch.cuda.synchronize()
         for name, a, b in zip(("sel", "o", "lse", "dq", "dk", "dv"), got, (sel_e, o, lse, *grads)):
-            if name in ("dk", "dv"):
-                a, b = a.float(), b.float()
-                assert (a - b).abs().max() <= 2.0 ** -7 * b.abs().max(), name
-                assert ((a - b).abs() <= 2.0 ** -7 * b.abs() + 1e-6).all(), name
-            else:
-                assert torch.equal(a, b), name
+            assert torch.equal(a, b), name
     meta.close()
 
 
@@ -290,3 +305,84 @@ def test_chunk_coherent_inputs_very_uneven_lists():
     sel = ref["sel"][0, 0]
     counts = np.bincount(sel[sel >= 0], minlength=lay.C)
     assert (counts == 0).sum() >= 3 and counts.max() >= 8 * 32              # empty lists and very long ones
+
+
+@pytest.mark.gpu
+def test_selection_rows_are_sets_forced_links_and_repeats_are_ignored():
+    """Rows handed to the attention calls from outside may name caption chunks, chunks of the query's own
+    window (both are forced links, attended anyway), a chunk twice, or chunk ids outside [0, C): the union
+    of forced and routed links is a set, so the result must equal the oracle's on the same rows."""
+    lay = mi.multishot_layout(3, 24, 3, 96, 32, "frame")        # 3 captions, 27 video chunks, windows of 3
+    B, H, d, topk, N = 1, 2, 128, 5, lay.N
+    q, k, v, d_o = mi.qkv_do(B, H, N, d, 81, "cpu", bf16_round=True)
+    qn, kn, vn, don = (t.numpy().astype(np.float64) for t in (q, k, v, d_o))
+    L = mo.OracleLayout.from_layout(lay)
+    rng = np.random.default_rng(7)
+    sel = rng.integers(-1, lay.C, size=(B, H, N, topk)).astype(np.int32)      # anything: text, own window, later chunks
+    sel[:, :, ::3, 2] = sel[:, :, ::3, 0]                                     # repeats
+    sel[:, :, 1::7, 4] = lay.C + 5                                            # out of range
+    sel[:, :, 5::11, 1] = -7
+    o_ref, lse_ref, _ = mo.attn_fwd(L, qn, kn, vn, np.where((sel < 0) | (sel >= lay.C), -1, sel))
+    sel_o = np.where((sel < 0) | (sel >= lay.C), -1, sel).astype(np.int32)
+    dq_ref = mo.attn_bwd_dq(L, qn, kn, vn, sel_o, o_ref, lse_ref, don)
+    dk_ref, dv_ref = mo.attn_bwd_dkdv(L, qn, kn, vn, sel_o, o_ref, lse_ref, don)
+    meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
+    qd, kd, vd, dod = (to_dev(t.numpy(), torch.bfloat16) for t in (q, k, v, d_o))
+    sel_d = torch.from_numpy(sel).to("cuda").contiguous()
+    o, lse = mb.attn_fwd(meta, qd, kd, vd, sel_d)
+    dq, dk, dv = mb.attn_bwd(meta, qd, kd, vd, o, lse, dod, sel_d)
+    torch.cuda.synchronize()
+    check_close("o", o.float().cpu().numpy(), o_ref)
+    check_close("lse", lse.cpu().numpy(), lse_ref)
+    check_close("dq", dq.float().cpu().numpy(), dq_ref)
+    check_close("dk", dk.float().cpu().numpy(), dk_ref)
+    check_close("dv", dv.float().cpu().numpy(), dv_ref)
+    meta.close()
+
+
+@pytest.mark.gpu
+def test_backward_after_forward_equals_plain_backward_and_falls_back():
+    """moc_attn_bwd_after_fwd reuses the forward's lists; with another workspace (no forward seen on it) it
+    rebuilds them. Both must equal moc_attn_bwd bit for bit."""
+    lay = mi.multishot_layout(2, 40, 3, 260, 130, "frame")
+    B, H, d, topk, N = 1, 3, 128, 3, lay.N
+    q, k, v, d_o = (t.to(torch.bfloat16).contiguous() for t in mi.qkv_do(B, H, N, d, 91, "cuda"))
+    meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
+    _, sel = mb.route(meta, q, k, topk)
+    ws = mb.attn_workspace(meta, B, H, d, topk, torch.bfloat16, True)
+    o, lse = mb.attn_fwd(meta, q, k, v, sel, None, ws)
+    plain = mb.attn_bwd(meta, q, k, v, o, lse, d_o, sel)
+    o, lse = mb.attn_fwd(meta, q, k, v, sel, None, ws)
+    reuse = mb.attn_bwd(meta, q, k, v, o, lse, d_o, sel, None, ws, None, after_fwd=True)
+    ws2 = mb.attn_workspace(meta, B, H, d, topk, torch.bfloat16, True)
+    ws2.fill_(0xFF)                                   # no lists in here: the call must build them
+    fresh = mb.attn_bwd(meta, q, k, v, o, lse, d_o, sel, None, ws2, None, after_fwd=True)
+    torch.cuda.synchronize()
+    for a, b, c in zip(plain, reuse, fresh):
+        assert torch.equal(a, b) and torch.equal(a, c)
+    meta.close()
+
+
+@pytest.mark.gpu
+def test_bad_scale_and_too_many_chunks_are_rejected_before_any_launch():
+    lay = mi.multishot_layout(1, 8, 2, 16, 8, "frame")
+    meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
+    q = torch.zeros(1, 1, lay.N, 64, dtype=torch.bfloat16, device="cuda")
+    sel = torch.full((1, 1, lay.N, 2), -1, dtype=torch.int32, device="cuda")
+    lse = torch.zeros(1, 1, lay.N, dtype=torch.float32, device="cuda")
+    for bad in (0.0, -0.1, float("nan"), float("inf")):
+        with pytest.raises(mb.MocError) as e:
+            mb.attn_fwd(meta, q, q, q, sel, bad)
+        assert e.value.status == -2
+        with pytest.raises(mb.MocError) as e:
+            mb.attn_bwd(meta, q, q, q, q, lse, q, sel, bad)
+        assert e.value.status == -2
+    meta.close()
+    # more chunks than the list builder's histogram holds: routing is refused, forced links alone still run
+    C = 16385
+    meta = mb.chunk_meta(np.arange(C + 1), np.zeros(C, np.int32), None, None)
+    with pytest.raises(mb.MocError) as e:
+        mb.attn_workspace(meta, 1, 1, 64, 2, torch.bfloat16, False)
+    assert e.value.status == -2
+    assert mb.attn_workspace(meta, 1, 1, 64, 0, torch.bfloat16, False).numel() > 0
+    meta.close()

@@ -195,6 +195,83 @@ def test_ds_rows_sum_to_zero_via_dq_of_constant_keys():
     assert np.abs(got["dq"]).max() < 1e-12
 
 
+# ---------------------------------------------------------------- 3b. subset modes
+
+@pytest.mark.parametrize("seed", range(4))
+@pytest.mark.parametrize("causal", [True, False])
+def test_query_and_chunk_subsets_equal_the_rows_of_the_full_run(seed, causal):
+    """The full-size GPU comparisons and the benchmark's CPU leg call the oracle on a list of queries
+    (`qidx`) or of key chunks (`chunks`). Those modes must give exactly the rows of the whole-sequence
+    run, which the brute-force tests above pin. For dK / dV the o and lse arrays are filled only at
+    the queries that attend a listed chunk, as the callers do."""
+    lay = mi.random_layout(500 + seed, n_chunks=14, max_len=11, n_shots=2, text_prob=0.25,
+                           window=["mixed", "chunk", "shot", "mixed"][seed])
+    d, topk, N = 8, 1 + seed, lay.N
+    q, k, v, d_o = (_rand((1, 2, N, d), 130 + 4 * seed + i) for i in range(4))
+    L = mo.OracleLayout.from_layout(lay)
+    full = mo.moc_layer(L, q, k, v, topk, causal, d_o)
+    rng = np.random.default_rng(seed)
+    qidx = np.sort(rng.choice(N, size=max(3, N // 4), replace=False)).astype(np.int32)
+    qidx[0], qidx[-1] = 0, N - 1                                       # first and last token always in
+    qidx = np.unique(qidx)
+    sel_s, scores, n_el = mo.route(L, q, full["kbar"], topk, causal, qidx, want_scores=True)
+    assert np.array_equal(sel_s, full["sel"][:, :, qidx])
+    _, scores_full, _ = mo.route(L, q, full["kbar"], topk, causal, want_scores=True)
+    assert np.array_equal(np.nan_to_num(scores, nan=-7e77), np.nan_to_num(scores_full[:, :, qidx], nan=-7e77))
+    o_s, lse_s, n_pairs = mo.attn_fwd(L, q, k, v, sel_s, None, qidx)
+    assert np.array_equal(o_s, full["o"][:, :, qidx]) and np.array_equal(lse_s, full["lse"][:, :, qidx])
+    dq_s = mo.attn_bwd_dq(L, q, k, v, sel_s, o_s, lse_s, d_o[:, :, qidx], None, qidx)
+    assert np.array_equal(dq_s, full["dq"][:, :, qidx])
+    # pair count of the subset = the explicit mask's count on those rows (head 0)
+    ref = bf.moc_bruteforce(lay, q[0, 0], k[0, 0], v[0, 0], topk, causal)
+    _, _, n0 = mo.attn_fwd(L, q[:, :1], k[:, :1], v[:, :1], sel_s[:, :1], None, qidx)
+    assert n0 == int(ref["mask"][qidx].sum())
+
+    chunks = np.sort(rng.choice(lay.C, size=3, replace=False)).astype(np.int32)
+    if L.kind.any():
+        chunks = np.unique(np.append(chunks, np.nonzero(L.kind)[0][0])).astype(np.int32)    # a caption chunk too
+    rows = np.concatenate([np.arange(L.off[j], L.off[j + 1]) for j in chunks])
+    o_part, lse_part = np.zeros_like(full["o"]), np.zeros_like(full["lse"])
+    for h in range(2):
+        att = np.zeros(N, bool)
+        for j in chunks:
+            att |= (L.kind[j] == 1) | (L.win[L.chunk_of] == L.win[j]) | (full["sel"][0, h] == j).any(-1)
+        o_part[0, h, att], lse_part[0, h, att] = full["o"][0, h, att], full["lse"][0, h, att]
+    dk_s, dv_s = mo.attn_bwd_dkdv(L, q, k, v, full["sel"], o_part, lse_part, d_o, None, chunks)
+    assert np.array_equal(dk_s[:, :, rows], full["dk"][:, :, rows])
+    assert np.array_equal(dv_s[:, :, rows], full["dv"][:, :, rows])
+    other = np.setdiff1d(np.arange(N), rows)
+    assert not dk_s[:, :, other].any() and not dv_s[:, :, other].any()
+
+
+def test_selection_rows_are_read_as_sets():
+    """A selection row handed to the attention functions may repeat a chunk or name a forced link;
+    the attended set is the union, so the result equals that of the cleaned row (and the brute-force mask)."""
+    lay = mi.multishot_layout(2, 6, 2, 10, 5, "frame")
+    d, N = 8, lay.N
+    q, k, v, d_o = (_rand((1, 1, N, d), 150 + i) for i in range(4))
+    L = mo.OracleLayout.from_layout(lay)
+    clean = np.full((1, 1, N, 3), -1, np.int32)
+    dirty = np.full((1, 1, N, 3), -1, np.int32)
+    text0 = int(np.nonzero(L.kind)[0][0])
+    for i in range(N):
+        own = L.chunk_of[i]
+        far = [j for j in range(lay.C) if L.kind[j] == 0 and L.win[j] != L.win[own]]
+        clean[0, 0, i, 0] = far[i % len(far)]
+        dirty[0, 0, i] = [far[i % len(far)], text0 if i % 2 else own, far[i % len(far)]]
+    a = mo.attn_fwd(L, q, k, v, clean)
+    b = mo.attn_fwd(L, q, k, v, dirty)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and a[2] == b[2]
+    mask = bf.token_mask(lay, clean[0, 0].astype(np.int64))
+    ref = bf.dense_masked_attention(q[0, 0], k[0, 0], v[0, 0], mask, d_o[0, 0])
+    np.testing.assert_allclose(b[0][0, 0], ref["o"], rtol=1e-9, atol=1e-12)
+    dq = mo.attn_bwd_dq(L, q, k, v, dirty, b[0], b[1], d_o)
+    dk, dv = mo.attn_bwd_dkdv(L, q, k, v, dirty, b[0], b[1], d_o)
+    np.testing.assert_allclose(dq[0, 0], ref["dq"], rtol=1e-6, atol=1e-9)
+    np.testing.assert_allclose(dk[0, 0], ref["dk"], rtol=1e-6, atol=1e-9)
+    np.testing.assert_allclose(dv[0, 0], ref["dv"], rtol=1e-6, atol=1e-9)
+
+
 # ---------------------------------------------------------------- 4. finite differences
 
 @pytest.mark.parametrize("seed", range(3))

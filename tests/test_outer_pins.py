@@ -81,21 +81,66 @@ def test_reduced_rows_keep_stream_order():
     assert (np.diff(rows) > 0).all()
 
 
-def test_segments_and_reduced_layout_bookkeeping():
-    """Layout helpers used with the outer loop: captions are segments of their own, a shot's video chunks
-    form one segment, and the reduced layout keeps chunk lengths, shots, windows and caption spans."""
+def test_segments_cut_at_captions_and_shots():
+    """Expected values written out by hand: 3 shots of [caption 8 | 2 frames x 16 tokens in chunks of 8]."""
     import moc_inputs as mi
     lay = mi.multishot_layout(3, 8, 2, 16, 8, "frame")
-    seg, cap = mi.shot_segments(lay)
+    seg, cap = ou.segments(lay.offsets, lay.shot, lay.text_spans)
     assert seg.tolist() == [0, 8, 40, 48, 80, 88, 120] and cap.tolist() == [1, 0, 1, 0, 1, 0]
+    # no captions: one segment per shot; a caption of two chunks is still one segment
+    seg, cap = ou.segments([0, 4, 8, 12, 20], [0, 0, 1, 1], np.zeros((0, 2), int))
+    assert seg.tolist() == [0, 8, 20] and cap.tolist() == [0, 0]
+    seg, cap = ou.segments([0, 4, 8, 12, 20], [0, 0, 0, 0], [[0, 8]])
+    assert seg.tolist() == [0, 8, 20] and cap.tolist() == [1, 0]
+
+
+def test_reduced_layout_by_hand_and_by_row_bookkeeping():
+    import moc_inputs as mi
+    lay = mi.multishot_layout(3, 8, 2, 16, 8, "frame")
+    seg, _ = ou.segments(lay.offsets, lay.shot, lay.text_spans)
     kept = [0, 2, 4, 5]
-    red = mi.reduce_layout(lay, seg, kept)
+    red = ou.reduce_layout(lay.offsets, lay.shot, lay.window, lay.text_spans, seg, kept)
+    # by hand: three captions of 8 tokens, then the last shot's 4 video chunks of 8
+    assert red["offsets"].tolist() == [0, 8, 16, 24, 32, 40, 48, 56]
+    assert red["shot"].tolist() == [0, 1, 2, 2, 2, 2, 2]
+    assert red["text_spans"].tolist() == [[0, 8], [8, 16], [16, 24]]
+    assert red["window"].tolist() == [lay.window[j] for j in (0, 5, 10, 11, 12, 13, 14)]
+    # every reduced chunk is an original chunk moved as a whole (checked through the row map)
     rows = ou.reduced_rows(seg, kept)
-    assert red.N == len(rows) == 8 + 8 + 8 + 32
-    # every reduced chunk is an original chunk, moved as a whole
-    src_chunk = np.searchsorted(lay.offsets, rows[red.offsets[:-1]], side="right") - 1
-    assert (np.diff(red.offsets) == np.diff(lay.offsets)[src_chunk]).all()
-    assert (red.shot == lay.shot[src_chunk]).all() and (red.window == lay.window[src_chunk]).all()
-    assert red.text_spans.tolist() == [[0, 8], [8, 16], [16, 24]]
+    assert int(red["offsets"][-1]) == len(rows)
+    src_chunk = np.searchsorted(lay.offsets, rows[red["offsets"][:-1]], side="right") - 1
+    assert (np.diff(red["offsets"]) == np.diff(lay.offsets)[src_chunk]).all()
+    assert (red["shot"] == lay.shot[src_chunk]).all() and (red["window"] == lay.window[src_chunk]).all()
+    # a caption span cut by a segment boundary keeps only the part inside the kept segment
+    red = ou.reduce_layout([0, 4, 8, 12], [0, 0, 0], None, [[0, 8]], [0, 4, 12], [1])
+    assert red["offsets"].tolist() == [0, 4, 8] and red["text_spans"].tolist() == [[0, 4]]
+    assert red["window"].tolist() == [1, 2]
     with pytest.raises(ValueError):
-        mi.reduce_layout(lay, np.array([0, 12, 120], np.int32), [0])     # 12 is not a chunk boundary
+        ou.reduce_layout(lay.offsets, lay.shot, lay.window, lay.text_spans, np.array([0, 12, 120]), [0])
+
+
+def test_host_layout_calls_agree_with_the_oracle_bookkeeping():
+    """moc_outer_segments / moc_reduce_layout (host-only entry points of the library) against the
+    oracle's independent versions on irregular layouts."""
+    import moc_inputs as mi
+    from paper_2508_21058_amd import binding as mb
+    for seed in range(12):
+        lay = mi.random_layout(400 + seed, n_chunks=14, max_len=9, n_shots=1 + seed % 4, text_prob=0.3,
+                               window=["mixed", "chunk", "shot"][seed % 3])
+        seg_o, cap_o = ou.segments(lay.offsets, lay.shot, lay.text_spans)
+        seg_l, cap_l = mb.outer_segments(lay.offsets, lay.shot, lay.text_spans)
+        assert seg_l.tolist() == seg_o.tolist() and cap_l.tolist() == cap_o.tolist()
+        rng = np.random.default_rng(seed)
+        P = len(seg_o) - 1
+        kept = sorted(rng.choice(P, size=int(rng.integers(1, P + 1)), replace=False).tolist())
+        red = ou.reduce_layout(lay.offsets, lay.shot, lay.window, lay.text_spans, seg_o, kept)
+        off, shot, win, spans, ranges = mb.reduce_layout(lay.offsets, lay.shot, lay.window, lay.text_spans, seg_l, kept)
+        assert off.tolist() == red["offsets"].tolist() and shot.tolist() == red["shot"].tolist()
+        assert win.tolist() == red["window"].tolist() and spans.tolist() == red["text_spans"].tolist()
+        assert ranges.tolist() == [[int(seg_o[j]), int(seg_o[j + 1] - seg_o[j])] for j in kept]
+    # errors: a segment boundary inside a chunk, kept out of order
+    lay = mi.multishot_layout(2, 8, 2, 16, 8, "frame")
+    with pytest.raises(mb.MocError):
+        mb.reduce_layout(lay.offsets, lay.shot, lay.window, lay.text_spans, [0, 12, lay.N], [0])
+    with pytest.raises(mb.MocError):
+        mb.reduce_layout(lay.offsets, lay.shot, lay.window, lay.text_spans, [0, 8, 40, lay.N], [1, 0])
