@@ -1,12 +1,10 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
 by element, on the same seeded inputs.
 
-Tolerances (bf16 matrix-core path): relative L2 error <= 1e-2 and, for every
-element, |error| <= 3e-2 * max(1, |reference element|): the stated absolute
-bound of 3e-2 wherever the reference value is at most 1 in magnitude, and the
-same bound relative to the element itself above that (a bf16 result of magnitude
-m carries a rounding step of m * 2^-8). The plain largest absolute error of
-every tensor is printed and collected (see conftest.py).
+Tolerances (bf16 matrix-core path): relative L2 error <= 1e-2 and largest
+absolute error <= 3e-2, unscaled, for o, lse, dq, dk and dv. The figures every
+comparison saw are printed and collected (see conftest.py); the largest
+absolute error over all tests is about 1.1e-2 (on gradients of magnitude 3-5).
 Pooled keys: relative error <= 1e-5. Selections: identical, order included,
 except where the oracle's scores tie within 1e-5 of the row's score scale.
 """
@@ -32,13 +30,11 @@ def check_close(name, got, ref):
     err = np.abs(got - ref)
     rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
     mabs = float(err.max()) if err.size else 0.0
-    lim = MAX_ABS * np.maximum(1.0, np.abs(ref))
-    worst = float((err / lim).max()) if err.size else 0.0
     big = float(np.abs(ref).max()) if ref.size else 0.0
     OBSERVED.append((name, rel, mabs, big))
-    print(f"[parity] {name}: rel_l2={rel:.3e} max_abs={mabs:.3e} max|ref|={big:.3e} worst/limit={worst:.3f}")
+    print(f"[parity] {name}: rel_l2={rel:.3e} max_abs={mabs:.3e} max|ref|={big:.3e}")
     assert rel <= REL_L2, f"{name}: rel_l2={rel:.3e}"
-    assert worst <= 1.0, f"{name}: max_abs={mabs:.3e}, an element is off by {worst:.2f}x its limit 3e-2*max(1,|ref|)"
+    assert mabs <= MAX_ABS, f"{name}: max_abs={mabs:.3e} (limit {MAX_ABS:.1e}, unscaled)"
     return rel, mabs
 
 
