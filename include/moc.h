@@ -116,6 +116,23 @@ int moc_route(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
               void *stream);
 
 /*
+ * moc_route for callers that cannot allocate device memory or carry a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc. Same arguments and results as moc_route (bit for bit), no
+ * workspace: the scratch that pass needs (the pooled keys split into three bf16
+ * planes, B * H * 3 * roundup(C, 32) * d * 2 bytes) lives in a static device
+ * array of MOC_STATIC_SCRATCH_BYTES that every GPU the library runs on holds
+ * until the process ends. Larger shapes are rejected with MOC_ERR_WORKSPACE.
+ * The call allocates nothing and frees nothing. All calls on one GPU share that
+ * array: calls that may overlap on one GPU (different streams or threads) race
+ * and must be serialised by the caller; calls on one stream are ordered.
+ */
+#define MOC_STATIC_SCRATCH_BYTES (16u << 20)
+int moc_route_static(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
+                     const void *q, const void *k, int32_t topk, int32_t causal,
+                     float *pooled_k, int32_t *sel, void *stream);
+
+/*
  * Routing with the two training-time regularisers of Sec. 3.2 ("Context
  * Drop-off", "Context Drop-in") applied to every (batch, head, query) row after
  * the top-k of moc_route:

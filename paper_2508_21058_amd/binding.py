@@ -23,7 +23,7 @@ MOC_BF16, MOC_F32 = 0, 1
 MOC_MAX_TOPK = 32
 
 SYMBOLS = ["moc_status_string", "moc_last_error", "moc_chunk_meta", "moc_meta_destroy", "moc_meta_copy_tables",
-           "moc_route_workspace_bytes", "moc_route", "moc_route_perturbed", "moc_outer_workspace_bytes", "moc_outer_route",
+           "moc_route_workspace_bytes", "moc_route", "moc_route_static", "moc_route_perturbed", "moc_outer_workspace_bytes", "moc_outer_route",
            "moc_outer_segments", "moc_reduce_layout", "moc_gather_rows", "moc_attn_workspace_bytes", "moc_attn_fwd",
            "moc_attn_bwd", "moc_attn_bwd_after_fwd",
            "moc_prof_enable", "moc_prof_read", "moc_probe"]
@@ -57,6 +57,7 @@ def lib():
     l.moc_meta_copy_tables.argtypes = [vp, vp, vp, vp]
     l.moc_route_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.c_int, C.POINTER(sz)]
     l.moc_route.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    l.moc_route_static.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, i32, i32, vp, vp, vp]
     l.moc_attn_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.c_int, C.c_int, C.POINTER(sz)]
     l.moc_attn_fwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, sz, vp]
     l.moc_attn_bwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, i32, C.c_float,
@@ -176,6 +177,19 @@ def route(meta: Meta, q: torch.Tensor, k: torch.Tensor, topk: int, causal: bool 
     sel = torch.empty(B, H, N, max(topk, 0), dtype=torch.int32, device=q.device)
     _check(lib().moc_route(meta.handle, B, H, d, dt, _ptr(q), _ptr(k), topk, int(bool(causal)), _ptr(pooled),
                            _ptr(sel) if topk > 0 else None, _ptr(ws), nbytes.value, _stream()), "moc_route")
+    return pooled, sel
+
+
+def route_static(meta: Meta, q: torch.Tensor, k: torch.Tensor, topk: int, causal: bool = True, out=None):
+    """moc_route_static: routing with the library's static scratch. `out` = (pooled_k, sel) tensors to fill
+    (the call itself allocates nothing; without `out` this wrapper allocates the two outputs)."""
+    B, H, N, d = _shape(meta, q)
+    _need_contig(q, k)
+    pooled, sel = out if out is not None else (
+        torch.empty(B, H, meta.C, d, dtype=torch.float32, device=q.device),
+        torch.empty(B, H, N, max(topk, 0), dtype=torch.int32, device=q.device))
+    _check(lib().moc_route_static(meta.handle, B, H, d, _dtype_code(q), _ptr(q), _ptr(k), topk, int(bool(causal)),
+                                  _ptr(pooled), _ptr(sel) if topk > 0 else None, _stream()), "moc_route_static")
     return pooled, sel
 
 

@@ -659,6 +659,61 @@ int moc_reduce_layout(int32_t C, const int32_t *off, const int32_t *shot, const 
     return MOC_OK;
 }
 
+namespace {
+// Scratch of moc_route_static: the three bf16 planes of the pooled keys. One copy per GPU, held
+// until the process ends. In host code the array's name is only a handle for hipGetSymbolAddress:
+// the device address is looked up once per device and every launch takes that pointer.
+constexpr size_t kStaticScratchBytes = (size_t)MOC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(MOC_ERR_HIP, "device ordinal out of range");
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!p) return fail(MOC_ERR_HIP, "hipGetSymbolAddress returned NULL");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOC_OK;
+}
+}  // namespace
+
+int moc_route_static(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
+                     int32_t topk, int32_t causal, float *pooled_k, int32_t *sel, void *stream) {
+    int rc = check_common(meta, B, H, d, topk, dtype);
+    if (rc) return rc;
+    if (!q || !k || !pooled_k || (!sel && topk > 0)) return fail(MOC_ERR_NULL, "q, k, pooled_k or sel is NULL");
+    if (misaligned(q) || misaligned(k) || misaligned(pooled_k) || misaligned(sel))
+        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    const moc::RouteWs RL = moc::route_ws_layout(meta, B * H, d, topk, dtype);
+    if (RL.total > kStaticScratchBytes)
+        return fail(MOC_ERR_WORKSPACE, "moc_route_static: B * H * 3 * roundup(C, 32) * d * 2 bytes exceed "
+                                       "MOC_STATIC_SCRATCH_BYTES; use moc_route with a workspace");
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    void *kb_split = static_cast<char *>(ws) + RL.kb_split;
+    // the pooling pass writes every row of the planes it is about to use (pad rows included), so
+    // nothing of an earlier call's contents is read
+    hipError_t e = moc::launch_pool(meta, B * H, d, dtype, k, pooled_k, kb_split, RL.Cpad, st);
+    if (e != hipSuccess) return hip_fail(e, "pool kernel");
+    if (topk > 0) {
+        e = moc::launch_route(meta, B * H, d, dtype, q, kb_split, RL.Cpad, topk, causal, sel, topk, st);
+        if (e != hipSuccess) return hip_fail(e, "route kernel");
+    }
+    return MOC_OK;
+}
+
 int moc_attn_workspace_bytes(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int32_t topk, int dtype,
                              int with_bwd, size_t *bytes) {
     if (!bytes) return fail(MOC_ERR_NULL, "bytes is NULL");

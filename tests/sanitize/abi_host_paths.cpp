@@ -65,6 +65,7 @@ int main() {
                                   0.1f, nullptr, nullptr, nullptr, nullptr, 0, nullptr) == MOC_ERR_NULL);
     EXPECT(moc_route_perturbed(nullptr, 1, 1, 128, 0, nullptr, nullptr, 4, 1, 0.5f, 1.f, 2, 1, nullptr, nullptr, nullptr,
                                0, nullptr) == MOC_ERR_NULL);
+    EXPECT(moc_route_static(nullptr, 1, 1, 128, 0, nullptr, nullptr, 4, 1, nullptr, nullptr, nullptr) == MOC_ERR_NULL);
     EXPECT(moc_meta_copy_tables(nullptr, nullptr, nullptr, nullptr) == MOC_ERR_NULL);
     EXPECT(moc_meta_destroy(nullptr) == MOC_OK);
 
