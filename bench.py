@@ -162,7 +162,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="eight", choices=["eight", "single", "tiny", "sweep", "short", "paper"])
+    ap.add_argument("--workload", default="eight", choices=["eight", "single", "tiny", "sweep", "short", "paper", "long"])
     ap.add_argument("--window", default=None, choices=[None, "frame", "shot", "chunk"])
     ap.add_argument("--chunk", type=int, default=None)
     ap.add_argument("--topk", type=int, default=None)

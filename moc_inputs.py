@@ -141,6 +141,42 @@ def stream_layout(n_shots: int, text_len: int, video_tokens: int, chunk: int, wi
                    n_shots=n_shots, text_len=text_len, video_tokens=video_tokens, chunk=chunk, window=window)
 
 
+def mixed_stream_layout(n_shots: int, text_len: int, video_tokens: int, sizes: Sequence[int],
+                        window: str = "shot", name: str = "") -> Layout:
+    """Per shot [caption span | video_tokens] with chunks of MIXED sizes in one stream: the video of a
+    shot is cut into chunks whose sizes cycle through ``sizes`` (the four sizes of the multi-shot
+    training schedule side by side, App. "Training Details"; Sec. 3.2: chunk lengths are highly
+    unequal), the shot's last chunk being whatever is left; shot s starts the cycle at sizes[s % len]."""
+    if window not in ("chunk", "shot"):
+        raise ValueError(window)
+    offs, shot, win, spans = [0], [], [], []
+    wid = 0
+    for s in range(n_shots):
+        if text_len > 0:
+            start = offs[-1]
+            offs.append(start + text_len)
+            spans.append((start, start + text_len))
+            shot.append(s)
+            win.append(wid)
+            if window == "chunk":
+                wid += 1
+        left, c = video_tokens, s
+        while left > 0:
+            m = min(int(sizes[c % len(sizes)]), left)
+            offs.append(offs[-1] + m)
+            shot.append(s)
+            win.append(wid)
+            if window == "chunk":
+                wid += 1
+            left -= m
+            c += 1
+        if window == "shot":
+            wid += 1
+    return _finish(name or f"{n_shots}shot_mixed_{window}", offs, shot, win, spans, n_shots=n_shots,
+                   text_len=text_len, video_tokens=video_tokens, chunk="mixed " + "/".join(str(x) for x in sizes),
+                   window=window)
+
+
 def random_layout(seed: int, n_chunks: int = 12, max_len: int = 40, n_shots: int = 2,
                   text_prob: float = 0.2, window: str = "mixed") -> Layout:
     """Small irregular layout for brute-force tests: chunk lengths 1..max_len,
@@ -199,6 +235,8 @@ def config_layout(cfg: str, window: Optional[str] = None, chunk: Optional[int] =
         return stream_layout(1, 256, 6000, chunk or 256, window or "chunk", "short")
     if cfg == "paper":       # multi-shot training set-up: 8 x (256 text + 14,040 video), chunk 10240 ... 1280, shot window
         return stream_layout(8, 256, 14040, chunk or 1280, window or "shot", "paper")
+    if cfg == "long":        # the paper's 8-shot scale: 8 x (256 text + 22,464 video) = 181,760 tokens, chunks of mixed sizes
+        return mixed_stream_layout(8, 256, 22464, (10240, 5120, 2560, 1280), window or "shot", "long")
     raise ValueError(cfg)
 
 
@@ -211,6 +249,8 @@ CONFIGS = {
     # the two training set-ups of App. "Training Details" (no causal mask in the single-shot one)
     "short":  dict(B=1, H=24, d=128, dtype="bf16", topk=3, causal=False),
     "paper":  dict(B=1, H=24, d=128, dtype="bf16", topk=5),
+    # Sec. 3.3 worked example / Sec. 4: 8 shots x ~23k tokens = ~180k tokens, k=5, shot window, mixed chunk sizes
+    "long":   dict(B=1, H=24, d=128, dtype="bf16", topk=5),
 }
 
 

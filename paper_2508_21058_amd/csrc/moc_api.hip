@@ -123,6 +123,7 @@ AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd)
     L.list_off = take((size_t)BH * (C + 1) * 4);
     L.tile_off = take((size_t)BH * (C + 1) * 4);
     L.vmask = take((size_t)BH * N * 4);
+    L.gsum = take((size_t)BH * 32 * C * 4);
     L.cnt_blk = take((size_t)BH * ((N + kRowsPerBlk - 1) / kRowsPerBlk) * C * 4);
     L.qlist = take((size_t)BH * N * std::max(topk, 1) * 4);
     L.plse = take((size_t)BH * N * slots * 4);
@@ -338,7 +339,8 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
                  o_wf = take((size_t)W * 4), o_wl = take((size_t)W * 4), o_aro = take((size_t)(W + 1) * 4),
                  o_ar = take(aranges.size() * sizeof(KeyRange)), o_at = take(atiles.size() * sizeof(AnchorTile)),
                  o_kv = take(kvitems.size() * sizeof(KvItem)), o_tt = take(ttiles.size() * sizeof(TextTile)),
-                 o_tm = take(textmask.size() * 4), o_ntb = take((size_t)(C + 1) * 4), o_cof = take((size_t)N * 4);
+                 o_tm = take(textmask.size() * 4), o_ntb = take((size_t)(C + 1) * 4), o_rw = take((size_t)C * 4),
+                 o_cof = take((size_t)N * 4);
     const size_t upload = o_cof;  // chunk_of is filled on the device
     std::vector<char> host(upload, 0);
     auto put = [&](size_t at, const void *src, size_t bytes) { if (bytes) std::memcpy(host.data() + at, src, bytes); };
@@ -356,6 +358,9 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
     std::vector<int32_t> ntb(C + 1, 0);
     for (int j = 0; j < C; ++j) ntb[j + 1] = ntb[j] + (kind[j] ? 0 : 1);
     put(o_ntb, ntb.data(), (size_t)(C + 1) * 4);
+    std::vector<int32_t> rwin(C);
+    for (int j = 0; j < C; ++j) rwin[j] = kind[j] ? -1 : win[j];
+    put(o_rw, rwin.data(), (size_t)C * 4);
 
     hipError_t e = hipMalloc(&m->d_base, o);
     if (e != hipSuccess) { delete m; return hip_fail(e, "hipMalloc(meta tables)"); }
@@ -373,6 +378,7 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
     m->d_text_tiles = reinterpret_cast<TextTile *>(base + o_tt);
     m->d_textmask = reinterpret_cast<uint32_t *>(base + o_tm);
     m->d_ntb = reinterpret_cast<int32_t *>(base + o_ntb);
+    m->d_rwin = reinterpret_cast<int32_t *>(base + o_rw);
     m->d_chunk_of = reinterpret_cast<int32_t *>(base + o_cof);
 
     hipStream_t st = static_cast<hipStream_t>(stream);

@@ -13,7 +13,7 @@ namespace moc {
 constexpr int kBM = 128;         // queries per workgroup in the query-stationary passes
 constexpr int kKeyTile = 128;    // keys per workgroup in the key-stationary pass (4 waves x 32)
 constexpr int kTextSeg = 8192;   // queries per partial of a text key tile in the key-stationary pass
-constexpr int kRowsPerBlk = 512; // queries per block of the list builder (one histogram row each)
+constexpr int kRowsPerBlk = 256; // queries per block of the list builder (one wave and one histogram column each)
 constexpr int kMaxListChunks = 16384;   // chunks the list builder's LDS histogram holds
 
 // One query tile of the forced-link pass: queries [q_start, q_start+q_count)
@@ -44,6 +44,7 @@ struct moc_meta {
     int32_t *d_off = nullptr;        // [C+1]
     int32_t *d_kind = nullptr;       // [C] 1 = text
     int32_t *d_win = nullptr;        // [C] dense window id
+    int32_t *d_rwin = nullptr;       // [C] window id of a video chunk, -1 for a caption chunk
     int32_t *d_wfirst = nullptr;     // [W] first chunk of window
     int32_t *d_wlast = nullptr;      // [W] last chunk of window (inclusive)
     int32_t *d_chunk_of = nullptr;   // [N]
@@ -92,7 +93,7 @@ hipError_t launch_probe(int kind, void *buf, size_t bytes, int iters, hipStream_
 
 // Layout of the attention workspace (byte offsets); shared by fwd and bwd.
 struct AttnWs {
-    size_t cnt, list_off, tile_off, vmask, cnt_blk, qlist, plse, po, delta, stats2, gstats2, tpart_k, tpart_v, total;
+    size_t cnt, list_off, tile_off, vmask, gsum, cnt_blk, qlist, plse, po, delta, stats2, gstats2, tpart_k, tpart_v, total;
 };
 AttnWs attn_ws_layout(const moc_meta *m, int BH, int d, int topk, bool with_bwd);
 

@@ -9,7 +9,7 @@
 // A stable counting sort on the device, no host synchronisation, no global
 // atomics, so every list is in ascending query order and the same input gives
 // the same lists (and the same summation order in dK / dV) on every call:
-//   count  one workgroup per block of kRowsPerBlk queries: which entries of a
+//   count  one wave per block of kRowsPerBlk queries: which entries of a
 //          row count at all (see entry_ok), an LDS histogram over the chunks,
 //          written out whole as row `block` of a [blocks][C] table;
 //   scan   down the blocks of every chunk (a block's first position inside the
@@ -31,63 +31,84 @@
 
 namespace moc {
 
-// slot r of the row `row` (topk entries) of a query whose chunk lies in window wq
-__device__ __forceinline__ bool entry_ok(const int32_t *row, int r, int C, const int32_t *kind, const int32_t *win,
-                                         int wq) {
-    const int j = row[r];
-    if (j < 0 || j >= C) return false;
-    if (kind[j] != 0 || win[j] == wq) return false;
-    for (int p = 0; p < r; ++p)
-        if (row[p] == j) return false;
-    return true;
-}
+// Both passes below walk a block of kRowsPerBlk queries 64 / topk queries at a time: lane L holds
+// entry L of the step's rows (query L / topk, slot L % topk), read with one coalesced load.
 
-__global__ __launch_bounds__(256) void list_count_kernel(const int32_t *__restrict__ sel, int N, int topk, int C,
-                                                         const int32_t *__restrict__ chunk_of,
-                                                         const int32_t *__restrict__ kind,
-                                                         const int32_t *__restrict__ win, int NB,
-                                                         uint32_t *__restrict__ vmask, int32_t *__restrict__ cnt_blk) {
-    extern __shared__ int32_t hist[];
-    const int bh = blockIdx.y, blk = blockIdx.x;
-    for (int b = threadIdx.x; b < C; b += 256) hist[b] = 0;
+// One wave per block. An entry counts if it names a video chunk (rw >= 0) outside the query's own
+// window that no earlier slot of the row names (the row-mates sit in the neighbouring lanes).
+__global__ __launch_bounds__(64) void list_count_kernel(const int32_t *__restrict__ sel, int N, int topk, int C,
+                                                        const int32_t *__restrict__ chunk_of,
+                                                        const int32_t *__restrict__ win,
+                                                        const int32_t *__restrict__ rw, int NB,
+                                                        uint32_t *__restrict__ vmask, int32_t *__restrict__ cnt_blk) {
+    extern __shared__ int32_t hist[];    // [C]
+    const int bh = blockIdx.y, blk = blockIdx.x, lane = threadIdx.x;
+    const int i0 = blk * kRowsPerBlk, nrow = min(kRowsPerBlk, N - i0);
+    for (int b = lane; b < C; b += 64) hist[b] = 0;
     __syncthreads();
-    const int i0 = blk * kRowsPerBlk;
-    for (int u = threadIdx.x; u < kRowsPerBlk; u += 256) {
-        const int i = i0 + u;
-        if (i >= N) break;
-        const int32_t *row = sel + ((size_t)bh * N + i) * topk;
-        const int wq = win[chunk_of[i]];
-        uint32_t mask = 0;
-        for (int r = 0; r < topk; ++r)
-            if (entry_ok(row, r, C, kind, win, wq)) {
-                mask |= 1u << r;
-                atomicAdd(&hist[row[r]], 1);
-            }
-        vmask[(size_t)bh * N + i] = mask;
+    const int rpb = 64 / topk;                     // queries per step (topk <= 32: at least two)
+    const int mu = lane / topk, r = lane - mu * topk;
+    const bool lane_on = mu < rpb;
+    const int32_t *src = sel + ((size_t)bh * N + i0) * topk;
+    uint32_t *vm = vmask + (size_t)bh * N + i0;
+    const uint32_t rowbits = topk >= 32 ? 0xffffffffu : ((1u << topk) - 1u);
+#pragma unroll 4
+    for (int u0 = 0; u0 < nrow; u0 += rpb) {
+        const int u = u0 + mu;
+        const bool in = lane_on && u < nrow;
+        const int j = in ? src[(size_t)u * topk + r] : -1;
+        const int wq = in ? win[chunk_of[i0 + u]] : -1;
+        bool ok = j >= 0 && j < C;
+        const int w = ok ? rw[j] : -1;
+        ok = ok && w >= 0 && w != wq;
+        for (int p = 0; p + 1 < topk; ++p) {
+            const int other = __shfl(j, mu * topk + p, 64);
+            if (p < r && other == j) ok = false;
+        }
+        if (ok) atomicAdd(&hist[j], 1);
+        const unsigned long long bal = __ballot(ok);
+        if (in && r == 0) vm[u] = (uint32_t)(bal >> (mu * topk)) & rowbits;
     }
     __syncthreads();
     int32_t *out = cnt_blk + ((size_t)bh * NB + blk) * C;
-    for (int b = threadIdx.x; b < C; b += 256) out[b] = hist[b];
+    for (int b = lane; b < C; b += 64) out[b] = hist[b];
 }
 
-// down the blocks: cnt_blk[bh][blk][j] becomes the number of entries of chunk j in earlier blocks
-__global__ __launch_bounds__(256) void list_block_scan_kernel(int32_t *__restrict__ cnt_blk, int NB, int C,
-                                                              int32_t *__restrict__ cnt) {
-    const int bh = blockIdx.y;
+// Down the blocks in two levels (the table is [block][chunk], so neighbouring threads read
+// neighbouring words): the blocks are cut into kScanGroups groups; pass 1 sums every chunk's
+// entries per group, pass 2 turns the group's entries into the number of entries of that chunk
+// in all earlier blocks and leaves the chunk's total behind.
+constexpr int kScanGroups = 32;
+__global__ __launch_bounds__(256) void list_group_sum_kernel(const int32_t *__restrict__ cnt_blk, int NB, int C,
+                                                             int32_t *__restrict__ gsum) {
+    const int bh = blockIdx.z, g = blockIdx.y;
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= C) return;
-    int32_t *col = cnt_blk + (size_t)bh * NB * C + j;
+    const int per = (NB + kScanGroups - 1) / kScanGroups;
+    const int b0 = g * per, b1 = min(NB, b0 + per);
+    const int32_t *col = cnt_blk + (size_t)bh * NB * C + j;
+    int sum = 0;
+    for (int b = b0; b < b1; ++b) sum += col[(size_t)b * C];
+    gsum[((size_t)bh * kScanGroups + g) * C + j] = sum;
+}
+__global__ __launch_bounds__(256) void list_block_scan_kernel(int32_t *__restrict__ cnt_blk, int NB, int C,
+                                                              const int32_t *__restrict__ gsum,
+                                                              int32_t *__restrict__ cnt) {
+    const int bh = blockIdx.z, g = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= C) return;
+    const int per = (NB + kScanGroups - 1) / kScanGroups;
+    const int b0 = g * per, b1 = min(NB, b0 + per);
+    const int32_t *gs = gsum + (size_t)bh * kScanGroups * C + j;
     int run = 0;
-    int b = 0;
-    for (; b + 8 <= NB; b += 8) {
-        int c[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) c[u] = col[(size_t)(b + u) * C];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) { col[(size_t)(b + u) * C] = run; run += c[u]; }
+    for (int u = 0; u < g; ++u) run += gs[(size_t)u * C];
+    int32_t *col = cnt_blk + (size_t)bh * NB * C + j;
+    for (int b = b0; b < b1; ++b) {
+        const int c = col[(size_t)b * C];
+        col[(size_t)b * C] = run;
+        run += c;
     }
-    for (; b < NB; ++b) { const int c = col[(size_t)b * C]; col[(size_t)b * C] = run; run += c; }
-    cnt[(size_t)bh * C + j] = run;
+    if (g == kScanGroups - 1) cnt[(size_t)bh * C + j] = run;
 }
 
 // per head: list_off = exclusive scan of cnt, tile_off = exclusive scan of ceil(cnt / kBM)
@@ -127,43 +148,46 @@ __global__ __launch_bounds__(256) void list_scan_kernel(const int32_t *__restric
     }
 }
 
-// One wave per block of queries. Lane r holds slot r of the current query; the slots that count
-// name distinct chunks, so the lanes of one LDS instruction never meet in a counter, and the
-// instructions of consecutive queries reach the counters in program order.
+// One wave per block. The positions are handed out query by query: one LDS instruction per query,
+// executed by that query's lanes only. The slots that count name distinct chunks, so the lanes of
+// one instruction never meet in a counter, and the instructions of consecutive queries reach the
+// counters in program order. All 64 lanes then store their entries with one instruction.
 __global__ __launch_bounds__(64) void list_fill_kernel(const int32_t *__restrict__ sel, int N, int topk, int C,
                                                        const uint32_t *__restrict__ vmask, int NB,
                                                        const int32_t *__restrict__ cnt_blk,
                                                        const int32_t *__restrict__ list_off,
                                                        int32_t *__restrict__ qlist) {
-    extern __shared__ int32_t cursor[];
+    extern __shared__ int32_t cursor[];  // [C]
     const int bh = blockIdx.y, blk = blockIdx.x, lane = threadIdx.x;
+    const int i0 = blk * kRowsPerBlk, nrow = min(kRowsPerBlk, N - i0);
     const int32_t *base = cnt_blk + ((size_t)bh * NB + blk) * C;
     const int32_t *lo = list_off + (size_t)bh * (C + 1);
     for (int b = lane; b < C; b += 64) cursor[b] = lo[b] + base[b];
     __syncthreads();
-    const int i0 = blk * kRowsPerBlk, i1 = min(N, i0 + kRowsPerBlk);
-    const int32_t *s = sel + (size_t)bh * N * topk;
-    const uint32_t *vm = vmask + (size_t)bh * N;
+    const int32_t *src = sel + ((size_t)bh * N + i0) * topk;
+    const uint32_t *vm = vmask + (size_t)bh * N + i0;
     int32_t *ql = qlist + (size_t)bh * N * topk;
-    const int r = lane & 31;
-    constexpr int U = 8;       // queries in flight
-    for (int i = i0; i < i1; i += U) {
-        int j[U], pos[U];
+    const int rpb = 64 / topk;
+    const int mu = lane / topk, r = lane - mu * topk;
+    const bool lane_on = mu < rpb;
+    constexpr int U = 4;                           // steps whose loads are in flight together
+    for (int u0 = 0; u0 < nrow; u0 += U * rpb) {
+        int j[U];
         bool ok[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int q = min(i + u, i1 - 1);
-            ok[u] = i + u < i1 && lane < topk && ((vm[q] >> r) & 1u);
-            j[u] = ok[u] ? s[(size_t)q * topk + r] : 0;
+        for (int t = 0; t < U; ++t) {
+            const int u = u0 + t * rpb + mu;
+            const bool in = lane_on && u < nrow;
+            ok[t] = in && ((vm[in ? u : 0] >> r) & 1u);
+            j[t] = in ? src[(size_t)u * topk + r] : 0;
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            pos[u] = 0;
-            if (ok[u]) pos[u] = atomicAdd(&cursor[j[u]], 1);
+        for (int t = 0; t < U; ++t) {
+            int pos = 0;
+            for (int v = 0; v < rpb; ++v)
+                if (ok[t] && mu == v) pos = atomicAdd(&cursor[j[t]], 1);
+            if (ok[t]) ql[pos] = ((i0 + u0 + t * rpb + mu) << 5) | r;
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (ok[u]) ql[pos[u]] = ((i + u) << 5) | r;
     }
 }
 
@@ -178,12 +202,15 @@ hipError_t launch_build_lists(const moc_meta *m, int BH, int topk, const int32_t
     int32_t *tile_off = reinterpret_cast<int32_t *>(ws + L.tile_off);
     int32_t *qlist = reinterpret_cast<int32_t *>(ws + L.qlist);
     MOC_PROF("build_lists", st);
-    const size_t shm = (size_t)C * 4;
-    list_count_kernel<<<dim3(NB, BH), dim3(256), shm, st>>>(sel, N, topk, C, m->d_chunk_of, m->d_kind, m->d_win, NB,
-                                                            vmask, cnt_blk);
-    list_block_scan_kernel<<<dim3((C + 255) / 256, BH), dim3(256), 0, st>>>(cnt_blk, NB, C, cnt);
+    const size_t shm_fill = (size_t)C * 4, shm_count = (size_t)C * 4;
+    list_count_kernel<<<dim3(NB, BH), dim3(64), shm_count, st>>>(sel, N, topk, C, m->d_chunk_of, m->d_win, m->d_rwin, NB,
+                                                                 vmask, cnt_blk);
+    int32_t *gsum = reinterpret_cast<int32_t *>(ws + L.gsum);
+    const dim3 sgrid((C + 255) / 256, kScanGroups, BH);
+    list_group_sum_kernel<<<sgrid, dim3(256), 0, st>>>(cnt_blk, NB, C, gsum);
+    list_block_scan_kernel<<<sgrid, dim3(256), 0, st>>>(cnt_blk, NB, C, gsum, cnt);
     list_scan_kernel<<<dim3(BH), dim3(256), 0, st>>>(cnt, C, list_off, tile_off);
-    list_fill_kernel<<<dim3(NB, BH), dim3(64), shm, st>>>(sel, N, topk, C, vmask, NB, cnt_blk, list_off, qlist);
+    list_fill_kernel<<<dim3(NB, BH), dim3(64), shm_fill, st>>>(sel, N, topk, C, vmask, NB, cnt_blk, list_off, qlist);
     return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=None, lay=None, cfg=None, n_chunks=2,
-         topk=None):
+         topk=None, pick_chunks=None):
     cfg = dict(cfg or mi.CONFIGS[workload])
     if topk is not None:
         cfg["topk"] = topk
@@ -65,7 +65,8 @@ def _run(workload, window, head, n_sample, with_text_chunk, seed=1234, chunk=Non
 
     rng = np.random.default_rng(5)
     video = np.nonzero(L.kind == 0)[0]
-    chunks = list(rng.choice(video[len(video) // 3:], size=n_chunks, replace=False))
+    chunks = list(pick_chunks) if pick_chunks is not None else \
+        list(rng.choice(video[len(video) // 3:], size=n_chunks, replace=False))
     if with_text_chunk:
         chunks.append(int(np.nonzero(L.kind == 1)[0][0]))
     chunks = np.array(sorted(chunks), dtype=np.int32)
@@ -162,3 +163,15 @@ def test_sweep_config_chunk_260_k2():
     """... and at its narrowest, with a caption chunk among the sampled key chunks: its 256 keys are attended by
     all 457,472 queries (56 query segments of partial sums and the fixed-order reduction)."""
     _run("sweep", "frame", head=4, n_sample=128, with_text_chunk=True, chunk=260, topk=2, n_chunks=1)
+
+
+def test_eight_shot_stream_of_180k_tokens_with_mixed_chunk_sizes():
+    """The paper's 8-shot scale (Sec. 3.3 worked example: ~180k tokens, k=5): 8 x (256 text + 22,464 video)
+    = 181,760 tokens, chunks of 10240 / 5120 / 2560 / 1280 tokens side by side in one stream (ragged tails),
+    whole-shot window. Chunks of every size are among the sampled key chunks."""
+    lay = mi.config_layout("long")
+    lens = np.diff(lay.offsets)
+    assert lay.N == 181760 and {10240, 5120, 2560, 1280} <= set(lens.tolist())
+    video = [j for j in range(lay.C // 2, lay.C) if lens[j] != 256]
+    pick = [next(j for j in video if lens[j] == m) for m in (10240, 5120, 2560, 1280)]
+    _run("long", None, head=13, n_sample=96, with_text_chunk=False, pick_chunks=pick)

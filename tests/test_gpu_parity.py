@@ -304,11 +304,14 @@ def test_chunk_coherent_inputs_very_uneven_lists():
 
 
 @pytest.mark.gpu
-def test_selection_rows_are_sets_forced_links_and_repeats_are_ignored():
+@pytest.mark.parametrize("window", ["frame", "shot"])
+def test_selection_rows_are_sets_forced_links_and_repeats_are_ignored(window):
     """Rows handed to the attention calls from outside may name caption chunks, chunks of the query's own
     window (both are forced links, attended anyway), a chunk twice, or chunk ids outside [0, C): the union
     of forced and routed links is a set, so the result must equal the oracle's on the same rows."""
-    lay = mi.multishot_layout(3, 24, 3, 96, 32, "frame")        # 3 captions, 27 video chunks, windows of 3
+    # 3 captions, 27 video chunks; windows of 3 chunks, or the whole shot with its caption (then a caption
+    # query's own window holds video chunks, which its row may not add a second time)
+    lay = mi.multishot_layout(3, 24, 3, 96, 32, window)
     B, H, d, topk, N = 1, 2, 128, 5, lay.N
     q, k, v, d_o = mi.qkv_do(B, H, N, d, 81, "cpu", bf16_round=True)
     qn, kn, vn, don = (t.numpy().astype(np.float64) for t in (q, k, v, d_o))
