@@ -175,6 +175,8 @@ def main():
     ap.add_argument("--outer", type=int, default=None, metavar="M",
                     help="time the outer-loop routing instead: segment means + top-M shots over [N, H d] features, "
                          "then the gather of q, k, v, dO into the reduced stream")
+    ap.add_argument("--fused-route", action="store_true",
+                    help="route with moc_route_fused (pooling, scoring and top-k in one launch) instead of moc_route")
     ap.add_argument("--no-secondary", dest="secondary", action="store_false",
                     help="skip the secondary rows (shot window, S2 inputs) that the default run of the benchmark workload adds")
     ap.add_argument("--inputs", default="S1", choices=["S1", "S2"],
@@ -279,6 +281,8 @@ def measure(args, lay, cfg, tensors, steps, warmup, perturb, use_graph, with_pro
         if ev: ev[0].record()
         if perturb:
             pooled, sel = mb.route_perturbed(meta, q, k, topk, causal, *perturb, args.seed)
+        elif args.fused_route:
+            pooled, sel = mb.route_fused(meta, q, k, topk, causal)
         else:
             pooled, sel = mb.route(meta, q, k, topk, causal)
         if ev: ev[1].record()
@@ -342,6 +346,7 @@ def measure(args, lay, cfg, tensors, steps, warmup, perturb, use_graph, with_pro
         "pool": ("byte", BH * (N * d * esz + lay.C * d * 4.0), None),
         "route_topk": ("byte", BH * (N * d * esz + lay.C * d * 4.0 + N * topk * 4.0), None),
         "route_perturb": ("byte", BH * N * (topk + width) * 4.0, None),
+        "route_fused": ("byte", BH * (2 * N * d * esz + lay.C * d * 4.0 + N * topk * 4.0), None),
     }
     traffic, tsrc = read_traffic(args.workload, lay.meta.get("window"))
     kernels = {}

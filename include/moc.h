@@ -133,6 +133,24 @@ int moc_route_static(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int 
                      float *pooled_k, int32_t *sel, void *stream);
 
 /*
+ * Stages (b)+(c) in ONE kernel launch (Sec. 5 names the fusion of routing as
+ * future work): same arguments, workspace and results as moc_route, bit for
+ * bit; bf16 tensors and topk >= 1 only. Inside the launch the first workgroups
+ * pool all chunks and every workgroup waits, for a bounded time, until the
+ * pooled keys are complete before it scores. The completion counter is a static
+ * device word of the library: fused launches must not overlap on one GPU.
+ * moc_route_fused_status (blocking) reports, and clears, whether any such wait
+ * ever ran out (then that call's sel is not valid); it never has in testing.
+ * On the benchmark shapes the fused launch is not faster than moc_route's two
+ * launches (figures in the design notes); moc_route stays the default.
+ */
+int moc_route_fused(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype,
+                    const void *q, const void *k, int32_t topk, int32_t causal,
+                    float *pooled_k, int32_t *sel, void *workspace, size_t workspace_bytes,
+                    void *stream);
+int moc_route_fused_status(int32_t *timed_out);
+
+/*
  * Routing with the two training-time regularisers of Sec. 3.2 ("Context
  * Drop-off", "Context Drop-in") applied to every (batch, head, query) row after
  * the top-k of moc_route:

@@ -23,7 +23,7 @@ MOC_BF16, MOC_F32 = 0, 1
 MOC_MAX_TOPK = 32
 
 SYMBOLS = ["moc_status_string", "moc_last_error", "moc_chunk_meta", "moc_meta_destroy", "moc_meta_copy_tables",
-           "moc_route_workspace_bytes", "moc_route", "moc_route_static", "moc_route_perturbed", "moc_outer_workspace_bytes", "moc_outer_route",
+           "moc_route_workspace_bytes", "moc_route", "moc_route_static", "moc_route_fused", "moc_route_fused_status", "moc_route_perturbed", "moc_outer_workspace_bytes", "moc_outer_route",
            "moc_outer_segments", "moc_reduce_layout", "moc_gather_rows", "moc_attn_workspace_bytes", "moc_attn_fwd",
            "moc_attn_bwd", "moc_attn_bwd_after_fwd",
            "moc_prof_enable", "moc_prof_read", "moc_probe"]
@@ -57,6 +57,8 @@ def lib():
     l.moc_meta_copy_tables.argtypes = [vp, vp, vp, vp]
     l.moc_route_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.c_int, C.POINTER(sz)]
     l.moc_route.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    l.moc_route_fused.argtypes = l.moc_route.argtypes
+    l.moc_route_fused_status.argtypes = [C.POINTER(i32)]
     l.moc_route_static.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, i32, i32, vp, vp, vp]
     l.moc_attn_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.c_int, C.c_int, C.POINTER(sz)]
     l.moc_attn_fwd.argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, sz, vp]
@@ -178,6 +180,28 @@ def route(meta: Meta, q: torch.Tensor, k: torch.Tensor, topk: int, causal: bool 
     _check(lib().moc_route(meta.handle, B, H, d, dt, _ptr(q), _ptr(k), topk, int(bool(causal)), _ptr(pooled),
                            _ptr(sel) if topk > 0 else None, _ptr(ws), nbytes.value, _stream()), "moc_route")
     return pooled, sel
+
+
+def route_fused(meta: Meta, q: torch.Tensor, k: torch.Tensor, topk: int, causal: bool = True):
+    """moc_route_fused: pooling, scoring and top-k in one launch -> pooled_k, sel (as route)."""
+    B, H, N, d = _shape(meta, q)
+    _need_contig(q, k)
+    dt = _dtype_code(q)
+    nbytes = C.c_size_t()
+    _check(lib().moc_route_workspace_bytes(meta.handle, B, H, d, topk, dt, C.byref(nbytes)),
+           "moc_route_workspace_bytes")
+    ws = torch.empty(max(nbytes.value, 16), dtype=torch.uint8, device=q.device)
+    pooled = torch.empty(B, H, meta.C, d, dtype=torch.float32, device=q.device)
+    sel = torch.empty(B, H, N, max(topk, 0), dtype=torch.int32, device=q.device)
+    _check(lib().moc_route_fused(meta.handle, B, H, d, dt, _ptr(q), _ptr(k), topk, int(bool(causal)), _ptr(pooled),
+                                 _ptr(sel), _ptr(ws), nbytes.value, _stream()), "moc_route_fused")
+    return pooled, sel
+
+
+def route_fused_timed_out() -> bool:
+    t = C.c_int32()
+    _check(lib().moc_route_fused_status(C.byref(t)), "moc_route_fused_status")
+    return bool(t.value)
 
 
 def route_static(meta: Meta, q: torch.Tensor, k: torch.Tensor, topk: int, causal: bool = True, out=None):

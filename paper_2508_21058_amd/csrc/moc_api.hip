@@ -442,6 +442,35 @@ int moc_route(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, 
     return MOC_OK;
 }
 
+int moc_route_fused(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
+                    int32_t topk, int32_t causal, float *pooled_k, int32_t *sel, void *workspace, size_t workspace_bytes,
+                    void *stream) {
+    int rc = check_common(meta, B, H, d, topk, dtype);
+    if (rc) return rc;
+    if (dtype != MOC_BF16) return fail(MOC_ERR_DTYPE, "moc_route_fused takes bf16 tensors");
+    if (topk < 1) return fail(MOC_ERR_SHAPE, "moc_route_fused needs topk >= 1");
+    if (!q || !k || !pooled_k || !sel) return fail(MOC_ERR_NULL, "q, k, pooled_k or sel is NULL");
+    if (misaligned(q) || misaligned(k) || misaligned(pooled_k) || misaligned(sel))
+        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    const moc::RouteWs RL = moc::route_ws_layout(meta, B * H, d, topk, dtype);
+    if (!workspace || workspace_bytes < RL.total) return fail(MOC_ERR_WORKSPACE, "route workspace too small");
+    if (misaligned(workspace)) return fail(MOC_ERR_ALIGN, "workspace must be 16-byte aligned");
+    void *kb_split = static_cast<char *>(workspace) + RL.kb_split;
+    hipError_t e = moc::launch_route_fused(meta, B * H, d, q, k, pooled_k, kb_split, RL.Cpad, topk, causal, sel,
+                                           static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "fused route kernel");
+    return MOC_OK;
+}
+
+int moc_route_fused_status(int32_t *timed_out) {
+    if (!timed_out) return fail(MOC_ERR_NULL, "timed_out is NULL");
+    int t = 0;
+    hipError_t e = moc::fused_wait_flag(&t);
+    if (e != hipSuccess) return hip_fail(e, "moc_route_fused_status");
+    *timed_out = t;
+    return MOC_OK;
+}
+
 int moc_route_perturbed(const moc_meta *meta, int32_t B, int32_t H, int32_t d, int dtype, const void *q, const void *k,
                         int32_t topk, int32_t causal, float p_max, float lambda, int32_t max_in, uint64_t seed,
                         float *pooled_k, int32_t *sel, void *workspace, size_t workspace_bytes, void *stream) {

@@ -110,6 +110,11 @@ hipError_t launch_pool(const moc_meta *m, int BH, int d, int dtype, const void *
 hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *kb_split, int Cpad,
                         int topk, int causal, int32_t *sel, int sel_stride, hipStream_t st);
 
+// pooling + scoring + top-k in one launch (bf16 storage); see route_fused_kernel
+hipError_t launch_route_fused(const moc_meta *m, int BH, int d, const void *q, const void *k, float *kbar,
+                              void *kb_split, int Cpad, int topk, int causal, int32_t *sel, hipStream_t st);
+hipError_t fused_wait_flag(int *timed_out);
+
 // counts -> offsets -> inverse lists (per head and chunk: the queries that routed to it)
 hipError_t launch_build_lists(const moc_meta *m, int BH, int topk, const int32_t *sel, char *ws,
                               const AttnWs &L, hipStream_t st);

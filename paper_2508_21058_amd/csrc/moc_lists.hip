@@ -52,7 +52,6 @@ __global__ __launch_bounds__(64) void list_count_kernel(const int32_t *__restric
     const int32_t *src = sel + ((size_t)bh * N + i0) * topk;
     uint32_t *vm = vmask + (size_t)bh * N + i0;
     const uint32_t rowbits = topk >= 32 ? 0xffffffffu : ((1u << topk) - 1u);
-#pragma unroll 4
     for (int u0 = 0; u0 < nrow; u0 += rpb) {
         const int u = u0 + mu;
         const bool in = lane_on && u < nrow;

@@ -6,6 +6,7 @@
 // the head-major layout so every wave reads whole 256-byte rows.
 #include "moc_device.h"
 #include "moc_internal.h"
+#include "moc_pool_unit.h"
 
 namespace moc {
 
@@ -27,80 +28,13 @@ hipError_t launch_chunk_of(const moc_meta *m, hipStream_t st) {
     return hipGetLastError();
 }
 
-// One workgroup per (chunk, head). Thread t owns 8 (bf16) or 4 (fp32) features
-// of every (256/TPR)-th row; partial sums are combined through LDS in a fixed
-// order, so the result does not depend on scheduling.
-// Besides the fp32 mean the kernel writes its exact split into three bf16
-// planes (hi + mid + lo == mean) for the matrix-core scoring pass; rows
-// C .. Cpad-1 of the planes are zero.
+// One workgroup per (chunk, head); see pool_unit.
 template <int D, typename T>
 __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ k, const int32_t *__restrict__ off,
                                                    int N, int C, int Cpad, float *__restrict__ kbar,
                                                    bf16_t *__restrict__ split) {
-    constexpr int VEC = 16 / sizeof(T);      // elements per 16-byte load
-    constexpr int TPR = D / VEC;             // threads per row
-    constexpr int RPP = 256 / TPR;           // rows per pass
-    const int j = blockIdx.x, bh = blockIdx.y;
-    if (j >= C) {
-        if (threadIdx.x < D) {
-#pragma unroll
-            for (int p = 0; p < 3; ++p) split[(((size_t)bh * 3 + p) * Cpad + j) * D + threadIdx.x] = (bf16_t)0.f;
-        }
-        return;
-    }
-    const int t0 = off[j], t1 = off[j + 1];
-    const int cg = threadIdx.x % TPR, r0 = threadIdx.x / TPR;
-    const T *base = k + ((size_t)bh * N) * D + cg * VEC;
-    float acc[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-    int t = t0 + r0;
-    // 4 independent loads in flight per lane
-    for (; t + 3 * RPP < t1; t += 4 * RPP) {
-        float f[4][8];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if constexpr (sizeof(T) == 2) {
-                Io<T>::load8f(base + (size_t)(t + u * RPP) * D, f[u]);
-            } else {
-                f32x4 x = *reinterpret_cast<const f32x4 *>(base + (size_t)(t + u * RPP) * D);
-                f[u][0] = x[0]; f[u][1] = x[1]; f[u][2] = x[2]; f[u][3] = x[3];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += f[u][e];
-    }
-    for (; t < t1; t += RPP) {
-        float f[8];
-        if constexpr (sizeof(T) == 2) {
-            Io<T>::load8f(base + (size_t)t * D, f);
-        } else {
-            f32x4 x = *reinterpret_cast<const f32x4 *>(base + (size_t)t * D);
-            f[0] = x[0]; f[1] = x[1]; f[2] = x[2]; f[3] = x[3];
-        }
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] += f[e];
-    }
-    __shared__ float red[RPP][D + 4];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) red[r0][cg * VEC + e] = acc[e];
-    __syncthreads();
-    if (threadIdx.x < D) {
-        float s = 0.f;
-#pragma unroll 4
-        for (int r = 0; r < RPP; ++r) s += red[r][threadIdx.x];
-        const float mean = s / (float)(t1 - t0);
-        kbar[((size_t)bh * C + j) * D + threadIdx.x] = mean;
-        const bf16_t hi = (bf16_t)mean;
-        const float r1 = mean - (float)hi;
-        const bf16_t mid = (bf16_t)r1;
-        const bf16_t lo = (bf16_t)(r1 - (float)mid);
-        split[(((size_t)bh * 3 + 0) * Cpad + j) * D + threadIdx.x] = hi;
-        split[(((size_t)bh * 3 + 1) * Cpad + j) * D + threadIdx.x] = mid;
-        split[(((size_t)bh * 3 + 2) * Cpad + j) * D + threadIdx.x] = lo;
-    }
+    __shared__ float red[PoolShape<D, T>::kRedFloats];
+    pool_unit<D, T>(k, off, N, C, Cpad, kbar, split, blockIdx.x, blockIdx.y, red);
 }
 
 hipError_t launch_pool(const moc_meta *m, int BH, int d, int dtype, const void *k, float *kbar, void *kb_split,

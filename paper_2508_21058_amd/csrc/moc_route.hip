@@ -20,6 +20,7 @@
 //   merge   the two half-waves exchange their lists.
 // One pass over the chunks; any data (ties, few tiles) stays exact.
 #include "moc_attn_common.h"
+#include "moc_pool_unit.h"
 
 namespace moc {
 
@@ -78,15 +79,13 @@ constexpr int kRouteThreads = 256;
 constexpr int kRouteStages = 2;
 
 template <int D, typename T, int KMAX>
-__global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void route_kernel(RouteArgs a) {
+__device__ __forceinline__ void route_body(const RouteArgs &a, char *smem, u32x2 (*queue)[kRouteThreads]) {
     constexpr int KS = D / 16;
     constexpr int NQ = sizeof(T) == 2 ? 1 : 3;       // query planes
     constexpr int PB = 32 * D * 2;                   // bytes of one plane tile (32 chunks)
     constexpr int TB = 3 * PB;                       // bytes of one staged tile
     constexpr int NWV = kRouteThreads / 64;
     constexpr int QPW = kRouteThreads / 2;           // queries per workgroup
-    __shared__ __attribute__((aligned(1024))) char smem[kRouteStages * TB];
-    __shared__ u32x2 queue[kQCap + 1][kRouteThreads];    // (score bits, chunk) pairs; row kQCap takes what does not fit
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
     const int bh = blockIdx.y, N = a.N, C = a.C;
@@ -308,6 +307,112 @@ __global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void r
         for (int p = 0; p < KMAX; ++p)
             if (p >= base) out[p - base] = idx[p];
     }
+}
+
+template <int D, typename T, int KMAX>
+__global__ __launch_bounds__(kRouteThreads, kRouteThreads == 256 ? 2 : 1) void route_kernel(RouteArgs a) {
+    __shared__ __attribute__((aligned(1024))) char smem[kRouteStages * 3 * 32 * D * 2];
+    __shared__ u32x2 queue[kQCap + 1][kRouteThreads];    // (score bits, chunk) pairs; row kQCap takes what does not fit
+    route_body<D, T, KMAX>(a, smem, queue);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pooling, scoring and top-k in ONE launch (the fusion the paper lists as future work, Sec. 5).
+// Every query needs the mean key of every earlier chunk, so the scoring part of every workgroup
+// depends on the whole pooling pass: the first kFusePoolWgs workgroups of the launch (they are
+// dispatched first and never wait before they pool) share the chunks among themselves, count the
+// chunks they have finished in a device word, and every workgroup waits for that count before it
+// scores. The wait is bounded (kFuseSpinLimit sleeps of a few hundred cycles): if it runs out, a
+// flag is raised, the workgroup scores whatever the planes hold, and every wave still exits.
+// The words live in a static device array (zero when the module loads); the last workgroup of a
+// launch clears them again, so launches must not overlap on one GPU.
+constexpr int kFusePoolWgs = 256;
+constexpr long long kFuseSpinLimit = 20000000;
+static __device__ unsigned int g_fuse_sync[4];       // [0] chunks pooled, [1] workgroups finished, [2] a wait ran out
+
+struct FuseArgs {
+    const void *k;
+    const int32_t *off;
+    float *kbar;
+    bf16_t *split;
+    unsigned int units;      // Cpad * BH (chunk, head) pairs to pool
+};
+
+template <int D, typename T, int KMAX>
+__global__ __launch_bounds__(kRouteThreads, 2) void route_fused_kernel(RouteArgs a, FuseArgs f) {
+    static_assert(kRouteThreads == 256, "the pooling unit is written for 256 threads");
+    __shared__ __attribute__((aligned(1024))) char smem[kRouteStages * 3 * 32 * D * 2];
+    __shared__ u32x2 queue[kQCap + 1][kRouteThreads];
+    static_assert(PoolShape<D, T>::kRedFloats * 4 <= kRouteStages * 3 * 32 * D * 2, "pooling scratch fits the tile buffers");
+    const unsigned int wg = blockIdx.y * gridDim.x + blockIdx.x, nwg = gridDim.x * gridDim.y;
+    const unsigned int npool = min(nwg, (unsigned int)kFusePoolWgs);
+    if (wg < npool) {
+        unsigned int done = 0;
+        for (unsigned int u = wg; u < f.units; u += npool) {
+            pool_unit<D, T>(static_cast<const T *>(f.k), f.off, a.N, a.C, a.Cpad, f.kbar, f.split, (int)(u % a.Cpad),
+                            (int)(u / a.Cpad), reinterpret_cast<float *>(smem));
+            ++done;
+        }
+        __syncthreads();                                       // every thread's stores are issued
+        if (threadIdx.x == 0)
+            __hip_atomic_fetch_add(&g_fuse_sync[0], done, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (threadIdx.x == 0) {
+        long long spins = 0;
+        while (__hip_atomic_load(&g_fuse_sync[0], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < f.units) {
+            if (++spins > kFuseSpinLimit) { g_fuse_sync[2] = 1u; break; }
+            __builtin_amdgcn_s_sleep(8);
+        }
+    }
+    __syncthreads();
+    route_body<D, T, KMAX>(a, smem, queue);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int fin = __hip_atomic_fetch_add(&g_fuse_sync[1], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (fin == nwg - 1) {                                  // the last one out: every workgroup is past its wait
+            __hip_atomic_store(&g_fuse_sync[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&g_fuse_sync[1], 0u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+hipError_t launch_route_fused(const moc_meta *m, int BH, int d, const void *q, const void *k, float *kbar,
+                              void *kb_split, int Cpad, int topk, int causal, int32_t *sel, hipStream_t st) {
+    RouteArgs a{};
+    a.q = q;
+    a.split = static_cast<const bf16_t *>(kb_split);
+    a.chunk_of = m->d_chunk_of; a.win = m->d_win; a.wfirst = m->d_wfirst; a.wlast = m->d_wlast;
+    a.textmask = m->d_textmask;
+    a.sel = sel;
+    a.N = m->N; a.C = m->C; a.Cpad = Cpad; a.topk = topk; a.causal = causal != 0;
+    a.stride = topk;
+    FuseArgs f{k, m->d_off, kbar, static_cast<bf16_t *>(kb_split), (unsigned int)Cpad * (unsigned int)BH};
+    dim3 grid((m->N + kRouteThreads / 2 - 1) / (kRouteThreads / 2), BH), block(kRouteThreads);
+    MOC_PROF("route_fused", st);
+#define MOC_FUSED(DD, KK) route_fused_kernel<DD, bf16_t, KK><<<grid, block, 0, st>>>(a, f)
+#define MOC_FUSED_K(DD)                         \
+    do {                                        \
+        if (topk <= 8) MOC_FUSED(DD, 8);        \
+        else if (topk <= 16) MOC_FUSED(DD, 16); \
+        else MOC_FUSED(DD, 32);                 \
+    } while (0)
+    if (d == 128) MOC_FUSED_K(128); else MOC_FUSED_K(64);
+#undef MOC_FUSED_K
+#undef MOC_FUSED
+    return hipGetLastError();
+}
+
+// blocking: has any wait of a fused launch run out since the module was loaded? (also clears the flag)
+hipError_t fused_wait_flag(int *timed_out) {
+    unsigned int w[4] = {};
+    hipError_t e = hipMemcpyFromSymbol(w, HIP_SYMBOL(g_fuse_sync), sizeof(w), 0, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return e;
+    *timed_out = w[2] != 0;
+    if (w[2]) {
+        const unsigned int zero = 0;
+        e = hipMemcpyToSymbol(HIP_SYMBOL(g_fuse_sync), &zero, sizeof(zero), 2 * sizeof(unsigned int), hipMemcpyHostToDevice);
+    }
+    return e;
 }
 
 hipError_t launch_route(const moc_meta *m, int BH, int d, int dtype, const void *q, const void *kb_split, int Cpad,

@@ -385,3 +385,23 @@ def test_bad_scale_and_too_many_chunks_are_rejected_before_any_launch():
     assert e.value.status == -2
     assert mb.attn_workspace(meta, 1, 1, 64, 0, torch.bfloat16, False).numel() > 0
     meta.close()
+
+
+@pytest.mark.gpu
+def test_fused_routing_launch_equals_the_two_launch_path():
+    """moc_route_fused (pooling, scoring and top-k in one launch, Sec. 5 future work) must give moc_route's
+    pooled keys and selections bit for bit, on repeated calls (its completion counter is reused), with
+    more chunks than pooling workgroups and with fewer, and no bounded wait may have run out."""
+    for lay, H, d, topk, causal in ((mi.multishot_layout(3, 40, 4, 520, 130, "frame"), 4, 128, 5, True),
+                                    (mi.multishot_layout(2, 16, 12, 96, 8, "frame"), 3, 64, 9, True),
+                                    (mi.multishot_layout(1, 32, 4, 256, 64, "chunk"), 2, 128, 3, False),
+                                    (mi.config_layout("single"), 24, 128, 5, True)):
+        q, k, _, _ = (t.to(torch.bfloat16).contiguous() for t in mi.qkv_do(1, H, lay.N, d, 23, "cuda"))
+        meta = mb.chunk_meta(lay.offsets, lay.shot, lay.window, lay.text_spans)
+        pooled_ref, sel_ref = mb.route(meta, q, k, topk, causal)
+        for _ in range(3):
+            pooled, sel = mb.route_fused(meta, q, k, topk, causal)
+            torch.cuda.synchronize()
+            assert torch.equal(pooled, pooled_ref) and torch.equal(sel, sel_ref)
+        meta.close()
+    assert not mb.route_fused_timed_out()
