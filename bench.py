@@ -386,9 +386,17 @@ def measure(args, lay, cfg, tensors, steps, warmup, perturb, use_graph, with_pro
         pbuf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         c_ms, c_bytes = mb.probe("copy", pbuf, 20)
         m_ms, m_flops = mb.probe("mfma", pbuf, 100000)
+        # matrix and vector work of different waves on one SIMD: alone and together (do they overlap?)
+        it = 20000
+        mix = {kind: mb.probe(kind, pbuf, it)[0] for kind in ("mfma4", "valu4", "mfma4+valu4", "mfma4+valu_same_wave")}
         del pbuf
         measured = {"hbm_copy_GBs": round(c_bytes / (c_ms * 1e-3) / 1e9, 1),
-                    "bf16_mfma_TFLOPs": round(m_flops / (m_ms * 1e-3) / 1e12, 1)}
+                    "bf16_mfma_TFLOPs": round(m_flops / (m_ms * 1e-3) / 1e12, 1),
+                    "mfma_valu_coissue": {"mfma_waves_alone_ms": round(mix["mfma4"], 3),
+                                          "valu_waves_alone_ms": round(mix["valu4"], 3),
+                                          "both_ms": round(mix["mfma4+valu4"], 3),
+                                          "both_in_one_wave_ms": round(mix["mfma4+valu_same_wave"], 3),
+                                          "both_over_sum": round(mix["mfma4+valu4"] / (mix["mfma4"] + mix["valu4"]), 3)}}
         roof["frac_of_measured"] = round(roof["achieved"] / (measured["bf16_mfma_TFLOPs"] if roof["bound"] == "mfma"
                                                              else measured["hbm_copy_GBs"]), 4)
 

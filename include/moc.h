@@ -325,7 +325,15 @@ int moc_prof_read(int32_t index, char *name, size_t name_cap, int32_t *launches,
  * launches, after one untimed pass) in *ms (host). Returns MOC_OK or a
  * negative moc_status; nothing is allocated on the device.
  */
-enum moc_probe_kind { MOC_PROBE_COPY = 0, MOC_PROBE_MFMA = 1 };
+enum moc_probe_kind {
+    MOC_PROBE_COPY = 0, MOC_PROBE_MFMA = 1,
+    /* Do matrix and vector instructions of different waves of one SIMD overlap? 8 waves on each of
+     * 256 workgroups; per iteration waves 0-3 issue 16 v_mfma_f32_32x32x16_bf16 each (kind 2),
+     * waves 4-7 issue 64 fma, 16 mul and 16 exp2 each (kind 3), or both run together (kind 4); kind 5
+     * puts that vector work into waves 0-3 themselves, interleaved with their matrix instructions.
+     * *units = iterations; compare the durations. buf as for MOC_PROBE_MFMA. */
+    MOC_PROBE_MFMA4 = 2, MOC_PROBE_VALU4 = 3, MOC_PROBE_MFMA4_VALU4 = 4, MOC_PROBE_MFMA4_VALU_SAME_WAVE = 5
+};
 int moc_probe(int32_t kind, void *buf, size_t bytes, int32_t iters, void *stream, float *ms, double *units);
 
 #ifdef __cplusplus

@@ -202,11 +202,11 @@ int moc_prof_read(int32_t index, char *name, size_t name_cap, int32_t *launches,
 
 int moc_probe(int32_t kind, void *buf, size_t bytes, int32_t iters, void *stream, float *ms, double *units) {
     if (!buf || !ms || !units) return fail(MOC_ERR_NULL, "moc_probe: NULL argument");
-    if (kind != MOC_PROBE_COPY && kind != MOC_PROBE_MFMA) return fail(MOC_ERR_SHAPE, "moc_probe: unknown kind");
+    if (kind < MOC_PROBE_COPY || kind > MOC_PROBE_MFMA4_VALU_SAME_WAVE) return fail(MOC_ERR_SHAPE, "moc_probe: unknown kind");
     if (iters <= 0) return fail(MOC_ERR_SHAPE, "moc_probe: iters must be positive");
     if (misaligned(buf)) return fail(MOC_ERR_ALIGN, "moc_probe: buffer must be 16-byte aligned");
     if (kind == MOC_PROBE_COPY && bytes < 32) return fail(MOC_ERR_WORKSPACE, "moc_probe: copy needs at least 32 bytes");
-    if (kind == MOC_PROBE_MFMA && bytes < (size_t)moc::kProbeMfmaGrid * 512 * sizeof(float))
+    if (kind != MOC_PROBE_COPY && bytes < (size_t)moc::kProbeMfmaGrid * 512 * sizeof(float))
         return fail(MOC_ERR_WORKSPACE, "moc_probe: mfma needs a 512 KiB buffer");
     hipEvent_t e0, e1;
     hipError_t e = hipEventCreate(&e0);
@@ -293,25 +293,30 @@ int moc_chunk_meta(int32_t N, int32_t C, const int32_t *off, const int32_t *shot
         for (int q0 = ws; q0 < we; q0 += kBM) atiles.push_back(AnchorTile{q0, std::min(kBM, we - q0), w, 0});
     }
 
-    // key-stationary backward items
+    // key-stationary backward items. Caption key tiles come first, ordered by query segment: the
+    // tiles that walk the same segment of queries are neighbours in the list, run at the same time
+    // on one XCD and share those Q / dO rows in its L2 instead of each fetching them from HBM.
     std::vector<KvItem> kvitems;
     std::vector<TextTile> ttiles;
     int n_partials = 0;
+    const int nseg = (N + kTextSeg - 1) / kTextSeg;
+    for (int j = 0; j < C; ++j)
+        if (kind[j])
+            for (int k0 = off[j]; k0 < off[j + 1]; k0 += kKeyTile) {
+                ttiles.push_back(TextTile{k0, std::min(kKeyTile, off[j + 1] - k0), n_partials, nseg});
+                n_partials += nseg;
+            }
+    for (int s = 0; s < nseg; ++s)
+        for (const TextTile &tt : ttiles)
+            kvitems.push_back(KvItem{tt.key_start, tt.key_len, s * kTextSeg, std::min(kTextSeg, N - s * kTextSeg), -1,
+                                     tt.first_partial + s, 0, 0});
     for (int j = 0; j < C; ++j) {
+        if (kind[j]) continue;
         for (int k0 = off[j]; k0 < off[j + 1]; k0 += kKeyTile) {
             const int klen = std::min(kKeyTile, off[j + 1] - k0);
-            if (kind[j]) {
-                const int nseg = (N + kTextSeg - 1) / kTextSeg;
-                ttiles.push_back(TextTile{k0, klen, n_partials, nseg});
-                for (int s = 0; s < nseg; ++s)
-                    kvitems.push_back(KvItem{k0, klen, s * kTextSeg, std::min(kTextSeg, N - s * kTextSeg), -1,
-                                             n_partials + s, 0, 0});
-                n_partials += nseg;
-            } else {
-                const int w = win[j];
-                const int ws = off[wfirst[w]], we = off[wlast[w] + 1];
-                kvitems.push_back(KvItem{k0, klen, ws, we - ws, j, -1, 0, 0});
-            }
+            const int w = win[j];
+            const int ws = off[wfirst[w]], we = off[wlast[w] + 1];
+            kvitems.push_back(KvItem{k0, klen, ws, we - ws, j, -1, 0, 0});
         }
     }
 

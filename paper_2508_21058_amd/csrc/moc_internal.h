@@ -12,7 +12,7 @@ namespace moc {
 
 constexpr int kBM = 128;         // queries per workgroup in the query-stationary passes
 constexpr int kKeyTile = 128;    // keys per workgroup in the key-stationary pass (4 waves x 32)
-constexpr int kTextSeg = 8192;   // queries per partial of a text key tile in the key-stationary pass
+constexpr int kTextSeg = 16384;   // queries per partial of a text key tile in the key-stationary pass
 constexpr int kRowsPerBlk = 256; // queries per block of the list builder (one wave and one histogram column each)
 constexpr int kMaxListChunks = 16384;   // chunks the list builder's LDS histogram holds
 

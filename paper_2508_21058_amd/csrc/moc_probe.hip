@@ -38,6 +38,73 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(float *__restrict__ out
     out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
 }
 
+// Do matrix and vector instructions of different waves on one SIMD run at the same time? Eight
+// waves per workgroup, one workgroup per compute unit (two waves per SIMD): waves 0-3 run MFMA
+// chains (mode bit 0), waves 4-7 run independent fma / exp2 chains (mode bit 1). Timed with
+// either role alone and with both, the three durations say whether the two kinds of work overlap
+// (both = max of the two) or take turns (both = sum). Mode bit 2 puts the vector work into the
+// MFMA waves themselves, interleaved with their matrix instructions (waves 4-7 idle).
+__global__ __launch_bounds__(512) void probe_mix_kernel(float *__restrict__ out, int iters, int mode) {
+    const int wave = threadIdx.x >> 6;
+    float s = 0.f;
+    if (wave < 4) {
+        if (mode & 1) {
+            bf16x8 a, b;
+            for (int i = 0; i < 8; ++i) {
+                a[i] = (__bf16)(1.f + 0.125f * ((threadIdx.x + i) & 3));
+                b[i] = (__bf16)(0.0078125f * (1 + ((threadIdx.x * 3 + i) & 7)));
+            }
+            f32x16 c0 = zero16(), c1 = zero16();
+            if (mode & 4) {
+                // the same vector work inside the MFMA wave itself, six vector instructions behind every MFMA
+                float x[16];
+                for (int i = 0; i < 16; ++i) x[i] = threadIdx.x * 0.001f + i;
+                for (int it = 0; it < iters; ++it) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        c0 = mfma32(a, b, c0);
+                        c1 = mfma32(b, a, c1);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) x[i] = __builtin_fmaf(x[i], 1.0001f, 0.5f);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) x[i] = __builtin_amdgcn_exp2f(x[i] * 0.001f);
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+                    }
+                }
+                for (int i = 0; i < 16; ++i) s += x[i];
+            } else {
+                for (int it = 0; it < iters; ++it) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        c0 = mfma32(a, b, c0);
+                        c1 = mfma32(b, a, c1);
+                    }
+                }
+            }
+            for (int i = 0; i < 16; ++i) s += c0[i] + c1[i];
+        }
+    } else if (mode & 2) {
+        float x[16];
+        for (int i = 0; i < 16; ++i) x[i] = threadIdx.x * 0.001f + i;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) x[i] = __builtin_fmaf(x[i], 1.0001f, 0.5f);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = __builtin_amdgcn_exp2f(x[i] * 0.001f);
+        }
+        for (int i = 0; i < 16; ++i) s += x[i];
+    }
+    out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
 // Runs one probe on `st` bracketed by the two events; `units` receives the bytes
 // moved (copy: read + written) or the flops issued (mfma) inside the bracket.
 hipError_t launch_probe(int kind, void *buf, size_t bytes, int iters, hipStream_t st, hipEvent_t e0, hipEvent_t e1,
@@ -52,6 +119,15 @@ hipError_t launch_probe(int kind, void *buf, size_t bytes, int iters, hipStream_
         for (int i = 0; i < iters; ++i) probe_copy_kernel<<<grid, 256, 0, st>>>(src, dst, n16);
         (void)hipEventRecord(e1, st);
         *units = 2.0 * 16.0 * (double)n16 * iters;
+    } else if (kind >= MOC_PROBE_MFMA4 && kind <= MOC_PROBE_MFMA4_VALU_SAME_WAVE) {
+        const int mode = kind == MOC_PROBE_MFMA4 ? 1 : (kind == MOC_PROBE_VALU4 ? 2 : (kind == MOC_PROBE_MFMA4_VALU4 ? 3 : 5));
+        const int grid = kProbeMfmaGrid;
+        probe_mix_kernel<<<grid, 512, 0, st>>>((float *)buf, 16, mode);  // untimed first pass
+        (void)hipEventRecord(e0, st);
+        probe_mix_kernel<<<grid, 512, 0, st>>>((float *)buf, iters, mode);
+        (void)hipEventRecord(e1, st);
+        // per iteration and wave: 16 MFMAs (waves 0-3), 64 fma + 16 mul + 16 exp2 (waves 4-7)
+        *units = (double)iters;
     } else {
         const int grid = kProbeMfmaGrid;                // one workgroup per compute unit
         probe_mfma_kernel<<<grid, 512, 0, st>>>((float *)buf, 16);       // untimed first pass
