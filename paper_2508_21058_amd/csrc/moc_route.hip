@@ -244,6 +244,13 @@ __device__ __forceinline__ void route_body(const RouteArgs &a, char *smem, u32x2
         // of either half is a lower bound of the k-th best of both, so the larger of the two bounds
         // serves both halves and about half as many scores reach the queues.
         tau = fmaxf(tau, xhalf(tau));
+        // With full lists (topk == KMAX) the two sorted lists give more: the k-th best of their union is
+        // the largest of min(mine[p], other[k - 2 - p]) over p (take p + 1 scores from one list and the
+        // rest from the other) and of the two tails above. Both halves see the same terms.
+        if (base == 0) {
+#pragma unroll
+            for (int p = 0; p + 1 < KMAX; ++p) tau = fmaxf(tau, fminf(val[p], xhalf(val[KMAX - 2 - p])));
+        }
     };
     auto scan = [&](auto cur, int t) {
         constexpr int CUR = decltype(cur)::value;
