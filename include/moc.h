@@ -209,7 +209,8 @@ int moc_route_perturbed(const moc_meta *meta, int32_t B, int32_t H, int32_t d, i
  * moc_gather_rows builds the reduced stream of any row-major tensor: src is
  * DEVICE [outer][n_src_rows][row_bytes], dst DEVICE [outer][sum of lengths]
  * [row_bytes]; ranges HOST [n_ranges][2] = (first row, length) in the order the
- * rows are to appear; row_bytes a multiple of 16; workspace DEVICE scratch of
+ * rows are to appear (a length of 0 is allowed and adds nothing; ranges may
+ * overlap or repeat); row_bytes a multiple of 16; workspace DEVICE scratch of
  * at least 16 * n_ranges bytes. Also returns after the copy has finished.
  *
  * Layout bookkeeping of the outer loop, host arrays only, no device work:

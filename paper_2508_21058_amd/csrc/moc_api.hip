@@ -606,22 +606,28 @@ int moc_gather_rows(int32_t outer, int32_t n_src_rows, int32_t row_bytes, const 
     if (outer <= 0 || n_src_rows <= 0 || n_ranges < 0) return fail(MOC_ERR_SHAPE, "outer, n_src_rows must be positive");
     if (row_bytes <= 0 || row_bytes % 16 != 0) return fail(MOC_ERR_SHAPE, "row_bytes must be a positive multiple of 16");
     if (n_ranges == 0) return MOC_OK;
-    if (!src || !dst || !ranges) return fail(MOC_ERR_NULL, "src, dst or ranges is NULL");
-    if (misaligned(src) || misaligned(dst) || misaligned(workspace))
-        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
-    if (!workspace || workspace_bytes < (size_t)n_ranges * 16) return fail(MOC_ERR_WORKSPACE, "need 16 bytes per range");
+    if (!ranges) return fail(MOC_ERR_NULL, "ranges is NULL");
+    // empty ranges contribute no rows and are left out of the device table
     std::vector<int32_t> tab((size_t)n_ranges * 4, 0);
     long long n_dst = 0;
+    int n_tab = 0;
     for (int r = 0; r < n_ranges; ++r) {
         const int32_t s0 = ranges[2 * r], len = ranges[2 * r + 1];
-        if (s0 < 0 || len <= 0 || (long long)s0 + len > n_src_rows) return fail(MOC_ERR_OFFSETS, "range outside the source");
+        if (s0 < 0 || len < 0 || (long long)s0 + len > n_src_rows) return fail(MOC_ERR_OFFSETS, "range outside the source");
+        if (len == 0) continue;
         if (n_dst + len >= (1LL << 31)) return fail(MOC_ERR_SHAPE, "reduced stream too long");
-        tab[4 * r] = s0; tab[4 * r + 1] = len; tab[4 * r + 2] = (int32_t)n_dst;
+        tab[4 * n_tab] = s0; tab[4 * n_tab + 1] = len; tab[4 * n_tab + 2] = (int32_t)n_dst;
         n_dst += len;
+        ++n_tab;
     }
+    if (n_tab == 0) return MOC_OK;
+    if (!src || !dst) return fail(MOC_ERR_NULL, "src or dst is NULL");
+    if (misaligned(src) || misaligned(dst) || misaligned(workspace))
+        return fail(MOC_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    if (!workspace || workspace_bytes < (size_t)n_tab * 16) return fail(MOC_ERR_WORKSPACE, "need 16 bytes per range");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = hipMemcpyAsync(workspace, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, st);
-    if (e == hipSuccess) e = moc::launch_gather(outer, n_src_rows, n_dst, row_bytes, src, dst, workspace, n_ranges, st);
+    hipError_t e = hipMemcpyAsync(workspace, tab.data(), (size_t)n_tab * 16, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = moc::launch_gather(outer, n_src_rows, n_dst, row_bytes, src, dst, workspace, n_tab, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);      // the table lives on this call's stack
     return e == hipSuccess ? MOC_OK : hip_fail(e, "moc_gather_rows");
 }

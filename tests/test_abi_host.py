@@ -124,3 +124,7 @@ def test_outer_route_and_gather_reject_bad_arguments_on_the_host():
     assert lib.moc_gather_rows(1, 100, 64, fake, 2, ok.ctypes.data, fake, fake, 16, None) == -7   # table does not fit
     assert lib.moc_gather_rows(1, 100, 64, None, 2, ok.ctypes.data, fake, fake, 64, None) == -1
     assert lib.moc_gather_rows(1, 100, 64, fake, 0, None, fake, fake, 0, None) == 0               # nothing to do
+    empty = np.array([[7, 0], [100, 0]], np.int32)                                  # empty ranges only: nothing to do either
+    assert lib.moc_gather_rows(1, 100, 64, None, 2, empty.ctypes.data, None, None, 0, None) == 0
+    neg = np.array([[7, -1]], np.int32)
+    assert lib.moc_gather_rows(1, 100, 64, fake, 1, neg.ctypes.data, fake, fake, 64, None) == -3

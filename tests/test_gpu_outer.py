@@ -67,6 +67,10 @@ def test_gather_is_exact_on_head_major_and_flat_tensors():
     flat = torch.randn(777, 40, device="cuda")
     got = mb.gather_rows(flat, [(5, 700), (0, 5)])
     assert torch.equal(got, torch.cat([flat[5:705], flat[0:5]]))
+    # empty ranges add nothing, overlapping ranges repeat their rows
+    got = mb.gather_rows(flat, [(9, 0), (5, 3), (777, 0), (6, 3), (0, 0)])
+    assert torch.equal(got, torch.cat([flat[5:8], flat[6:9]]))
+    assert mb.gather_rows(flat, [(9, 0)]).shape == (0, 40)
 
 
 def test_full_size_stream_of_the_benchmark_layout():

@@ -37,7 +37,7 @@ def _case(lay, H, d, topk, causal, p_max, lam, max_in, seed, dtype=torch.bfloat1
     got = sel.cpu().numpy()[:, heads][:, :, qi]
     base_gpu = base.cpu().numpy()[:, heads][:, :, qi] if topk > 0 else base_ref
     comparable = (base_gpu == base_ref).all(-1) if topk > 0 else np.ones(got.shape[:3], bool)
-    assert comparable.mean() > 0.999
+    assert (~comparable).sum() <= max(1, comparable.size // 1000)     # rows where routing itself hit a tolerated tie
     assert (got[comparable] == want[comparable]).all(), \
         f"{(got[comparable] != want[comparable]).any(-1).sum()} rows differ"
     meta.close()
