@@ -31,7 +31,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # vector instructions per matrix instruction in the score + top-k pass, from the counter run recorded in
 # profiles/moc_kernels_eight_shot_frame_window_counters.txt (SQ_INSTS_VALU / SQ_INSTS_MFMA)
-ROUTE_VALU_PER_MFMA = 23.4
+ROUTE_VALU_PER_MFMA = 22.0
 
 
 def layout_counts(lay, sel, chunk_of_t, topk, causal=True):
