@@ -389,6 +389,12 @@ def measure(args, lay, cfg, tensors, steps, warmup, perturb, use_graph, with_pro
         # matrix and vector work of different waves on one SIMD: alone and together (do they overlap?)
         it = 20000
         mix = {kind: mb.probe(kind, pbuf, it)[0] for kind in ("mfma4", "valu4", "mfma4+valu4", "mfma4+valu_same_wave")}
+        # data paths inside a compute unit (bytes per clock and CU at the nominal 2.4 GHz): LDS operand reads, and
+        # the global -> LDS tile copies from cache-resident data, asynchronous (as the kernels do) or via registers
+        cu = {}
+        for kind in ("lds_read", "lds_read_transposed", "copy_to_lds_async", "copy_via_registers"):
+            p_ms, p_bytes = mb.probe(kind, pbuf, 2000)
+            cu[kind + "_B_per_clk_cu"] = round(p_bytes / 256 / (p_ms * 1e-3 * 2.4e9), 1)
         del pbuf
         measured = {"hbm_copy_GBs": round(c_bytes / (c_ms * 1e-3) / 1e9, 1),
                     "bf16_mfma_TFLOPs": round(m_flops / (m_ms * 1e-3) / 1e12, 1),
@@ -396,7 +402,8 @@ def measure(args, lay, cfg, tensors, steps, warmup, perturb, use_graph, with_pro
                                           "valu_waves_alone_ms": round(mix["valu4"], 3),
                                           "both_ms": round(mix["mfma4+valu4"], 3),
                                           "both_in_one_wave_ms": round(mix["mfma4+valu_same_wave"], 3),
-                                          "both_over_sum": round(mix["mfma4+valu4"] / (mix["mfma4"] + mix["valu4"]), 3)}}
+                                          "both_over_sum": round(mix["mfma4+valu4"] / (mix["mfma4"] + mix["valu4"]), 3)},
+                    "cu_data_paths": cu}
         roof["frac_of_measured"] = round(roof["achieved"] / (measured["bf16_mfma_TFLOPs"] if roof["bound"] == "mfma"
                                                              else measured["hbm_copy_GBs"]), 4)
 

@@ -333,7 +333,14 @@ enum moc_probe_kind {
      * waves 4-7 issue 64 fma, 16 mul and 16 exp2 each (kind 3), or both run together (kind 4); kind 5
      * puts that vector work into waves 0-3 themselves, interleaved with their matrix instructions.
      * *units = iterations; compare the durations. buf as for MOC_PROBE_MFMA. */
-    MOC_PROBE_MFMA4 = 2, MOC_PROBE_VALU4 = 3, MOC_PROBE_MFMA4_VALU4 = 4, MOC_PROBE_MFMA4_VALU_SAME_WAVE = 5
+    MOC_PROBE_MFMA4 = 2, MOC_PROBE_VALU4 = 3, MOC_PROBE_MFMA4_VALU4 = 4, MOC_PROBE_MFMA4_VALU_SAME_WAVE = 5,
+    /* Data paths inside a compute unit, two workgroups of four waves on each: every wave re-reads 16 KB
+     * of LDS per iteration with ds_read_b128 (kind 6) or 8 KB with ds_read_b64_tr_b16 (kind 7), or copies
+     * 16 KB per iteration from a cache-resident 64 KB at the start of `buf` into LDS, with
+     * global_load_lds_dwordx4 (kind 8) or through registers (kind 9). *units = bytes moved over all
+     * compute units. buf >= 1 MiB (its first 64 KB are read, the rest receives one word per lane). */
+    MOC_PROBE_LDS_READ = 6, MOC_PROBE_LDS_READ_TRANSPOSED = 7, MOC_PROBE_COPY_TO_LDS_ASYNC = 8,
+    MOC_PROBE_COPY_VIA_REGISTERS = 9
 };
 int moc_probe(int32_t kind, void *buf, size_t bytes, int32_t iters, void *stream, float *ms, double *units);
 

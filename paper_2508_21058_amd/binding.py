@@ -297,12 +297,16 @@ def prof_read():
     return out
 
 
+_PROBE_KINDS = {"copy": 0, "mfma": 1, "mfma4": 2, "valu4": 3, "mfma4+valu4": 4, "mfma4+valu_same_wave": 5,
+                "lds_read": 6, "lds_read_transposed": 7, "copy_to_lds_async": 8, "copy_via_registers": 9}
+
+
 def probe(kind: str, buf: torch.Tensor, iters: int):
     """Machine probe: kind 'copy' streams the first half of `buf` into the second, 'mfma' runs
     a loop of independent bf16 MFMA chains. -> (milliseconds, bytes moved or flops issued)."""
     assert buf.is_cuda and buf.is_contiguous()
     ms, units = C.c_float(), C.c_double()
-    _check(lib().moc_probe({"copy": 0, "mfma": 1, "mfma4": 2, "valu4": 3, "mfma4+valu4": 4, "mfma4+valu_same_wave": 5}[kind], _ptr(buf), buf.numel() * buf.element_size(),
+    _check(lib().moc_probe(_PROBE_KINDS[kind], _ptr(buf), buf.numel() * buf.element_size(),
                            int(iters), _stream(), C.byref(ms), C.byref(units)), "moc_probe")
     return ms.value, units.value
 

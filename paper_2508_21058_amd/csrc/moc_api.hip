@@ -202,12 +202,14 @@ int moc_prof_read(int32_t index, char *name, size_t name_cap, int32_t *launches,
 
 int moc_probe(int32_t kind, void *buf, size_t bytes, int32_t iters, void *stream, float *ms, double *units) {
     if (!buf || !ms || !units) return fail(MOC_ERR_NULL, "moc_probe: NULL argument");
-    if (kind < MOC_PROBE_COPY || kind > MOC_PROBE_MFMA4_VALU_SAME_WAVE) return fail(MOC_ERR_SHAPE, "moc_probe: unknown kind");
+    if (kind < MOC_PROBE_COPY || kind > MOC_PROBE_COPY_VIA_REGISTERS) return fail(MOC_ERR_SHAPE, "moc_probe: unknown kind");
     if (iters <= 0) return fail(MOC_ERR_SHAPE, "moc_probe: iters must be positive");
     if (misaligned(buf)) return fail(MOC_ERR_ALIGN, "moc_probe: buffer must be 16-byte aligned");
     if (kind == MOC_PROBE_COPY && bytes < 32) return fail(MOC_ERR_WORKSPACE, "moc_probe: copy needs at least 32 bytes");
     if (kind != MOC_PROBE_COPY && bytes < (size_t)moc::kProbeMfmaGrid * 512 * sizeof(float))
         return fail(MOC_ERR_WORKSPACE, "moc_probe: mfma needs a 512 KiB buffer");
+    if (kind >= MOC_PROBE_LDS_READ && bytes < ((size_t)1 << 20))
+        return fail(MOC_ERR_WORKSPACE, "moc_probe: the compute-unit probes need a 1 MiB buffer");
     hipEvent_t e0, e1;
     hipError_t e = hipEventCreate(&e0);
     if (e != hipSuccess) return hip_fail(e, "moc_probe");

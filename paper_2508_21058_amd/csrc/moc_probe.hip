@@ -105,6 +105,58 @@ __global__ __launch_bounds__(512) void probe_mix_kernel(float *__restrict__ out,
     out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
 }
 
+// On-chip data paths of one compute unit, two workgroups of four waves per CU as in the query-stationary
+// attention kernels. MODE 0 / 1: every wave re-reads its own 16 KB of LDS with ds_read_b128 /
+// ds_read_b64_tr_b16 (the two operand reads of the attention kernels). MODE 2 / 3: every wave copies
+// 16 KB per iteration from a cache-resident 64 KB of global memory into LDS, with the asynchronous
+// global_load_lds_dwordx4 the kernels use, or through registers (global_load_dwordx4 + ds_write_b128).
+template <int MODE>
+__global__ __launch_bounds__(256) void probe_cu_path_kernel(const uint32_t *__restrict__ src, uint32_t *__restrict__ out,
+                                                            int iters) {
+    __shared__ __attribute__((aligned(1024))) uint32_t lds[16384];       // 64 KB
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < 16384; i += 256) lds[i] = i;
+    __syncthreads();
+    uint32_t *mine = lds + wave * 4096;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    if (MODE == 0 || MODE == 1) {
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                if (MODE == 0) {
+                    acc += *reinterpret_cast<const u32x4 *>(mine + ((u * 256 + lane * 4) & 4095));
+                } else {
+                    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+                    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(mine + ((u * 128 + lane * 2) & 4095)));
+                    acc[0] += (uint32_t)v[0];
+                    acc[1] += (uint32_t)v[1];
+                }
+            }
+            asm volatile("" : "+v"(acc));
+        }
+    } else {
+        const uint32_t *g = src + wave * 4096 + lane * 4;
+        for (int it = 0; it < iters; ++it) {
+            if (MODE == 2) {
+#pragma unroll
+                for (int u = 0; u < 16; ++u) async_copy16_at(g + u * 256, lds_address(mine + u * 256));
+                wait_vmcnt<0>();
+            } else {
+                u32x4 v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = *reinterpret_cast<const u32x4 *>(g + u * 256);
+#pragma unroll
+                for (int u = 0; u < 16; ++u) *reinterpret_cast<u32x4 *>(mine + u * 256 + lane * 4) = v[u];
+                wait_lgkm0();
+            }
+            asm volatile("" ::: "memory");
+        }
+        __syncthreads();
+        acc[0] = lds[threadIdx.x];
+    }
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = acc[0] + acc[1] + acc[2] + acc[3];
+}
+
 // Runs one probe on `st` bracketed by the two events; `units` receives the bytes
 // moved (copy: read + written) or the flops issued (mfma) inside the bracket.
 hipError_t launch_probe(int kind, void *buf, size_t bytes, int iters, hipStream_t st, hipEvent_t e0, hipEvent_t e1,
@@ -128,6 +180,22 @@ hipError_t launch_probe(int kind, void *buf, size_t bytes, int iters, hipStream_
         (void)hipEventRecord(e1, st);
         // per iteration and wave: 16 MFMAs (waves 0-3), 64 fma + 16 mul + 16 exp2 (waves 4-7)
         *units = (double)iters;
+    } else if (kind >= MOC_PROBE_LDS_READ && kind <= MOC_PROBE_COPY_VIA_REGISTERS) {
+        const int grid = 2 * kProbeMfmaGrid;            // two workgroups per compute unit
+        const uint32_t *src = static_cast<const uint32_t *>(buf);
+        uint32_t *out = static_cast<uint32_t *>(buf) + 16384;            // behind the 64 KB that are read
+        auto go = [&](int n) {
+            if (kind == MOC_PROBE_LDS_READ) probe_cu_path_kernel<0><<<grid, 256, 0, st>>>(src, out, n);
+            else if (kind == MOC_PROBE_LDS_READ_TRANSPOSED) probe_cu_path_kernel<1><<<grid, 256, 0, st>>>(src, out, n);
+            else if (kind == MOC_PROBE_COPY_TO_LDS_ASYNC) probe_cu_path_kernel<2><<<grid, 256, 0, st>>>(src, out, n);
+            else probe_cu_path_kernel<3><<<grid, 256, 0, st>>>(src, out, n);
+        };
+        go(4);                                          // untimed first pass
+        (void)hipEventRecord(e0, st);
+        go(iters);
+        (void)hipEventRecord(e1, st);
+        // per iteration a wave moves 16 KB (8 KB with the 8-byte transposed reads), 4 waves per workgroup
+        *units = (double)grid * 4.0 * (kind == MOC_PROBE_LDS_READ_TRANSPOSED ? 8192.0 : 16384.0) * (double)iters;
     } else {
         const int grid = kProbeMfmaGrid;                // one workgroup per compute unit
         probe_mfma_kernel<<<grid, 512, 0, st>>>((float *)buf, 16);       // untimed first pass

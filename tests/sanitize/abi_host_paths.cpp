@@ -74,7 +74,7 @@ int main() {
     double units = 0.0;
     void *fake = (void *)0x1000;         // never dereferenced: every call below is rejected on the host
     EXPECT(moc_probe(0, nullptr, 64, 1, nullptr, &ms, &units) == MOC_ERR_NULL);
-    EXPECT(moc_probe(7, fake, 64, 1, nullptr, &ms, &units) == MOC_ERR_SHAPE);
+    EXPECT(moc_probe(10, fake, 64, 1, nullptr, &ms, &units) == MOC_ERR_SHAPE);
     EXPECT(moc_probe(0, fake, 64, 0, nullptr, &ms, &units) == MOC_ERR_SHAPE);
     EXPECT(moc_probe(0, (void *)0x1004, 64, 1, nullptr, &ms, &units) == MOC_ERR_ALIGN);
     EXPECT(moc_probe(0, fake, 16, 1, nullptr, &ms, &units) == MOC_ERR_WORKSPACE);

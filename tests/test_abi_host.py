@@ -83,7 +83,8 @@ def test_probe_rejects_bad_arguments_before_any_launch():
     ms, units = C.c_float(), C.c_double()
     assert lib.moc_probe(0, None, C.c_size_t(64), 1, None, C.byref(ms), C.byref(units)) == -1
     fake = C.c_void_p(0x1000)                       # never dereferenced: every call below is rejected on the host
-    assert lib.moc_probe(7, fake, C.c_size_t(64), 1, None, C.byref(ms), C.byref(units)) == -2
+    assert lib.moc_probe(10, fake, C.c_size_t(64), 1, None, C.byref(ms), C.byref(units)) == -2
+    assert lib.moc_probe(8, fake, C.c_size_t(600000), 1, None, C.byref(ms), C.byref(units)) == -7   # needs 1 MiB
     assert lib.moc_probe(4, fake, C.c_size_t(4096), 1, None, C.byref(ms), C.byref(units)) == -7
     assert lib.moc_probe(0, fake, C.c_size_t(64), 0, None, C.byref(ms), C.byref(units)) == -2
     assert lib.moc_probe(0, C.c_void_p(0x1004), C.c_size_t(64), 1, None, C.byref(ms), C.byref(units)) == -8

@@ -263,6 +263,11 @@ def test_probes_copy_exactly_and_report_plausible_rates():
     assert nbytes == 3 * 2.0 * (1 << 25) and 0 < nbytes / (ms * 1e-3) < 8.0e12
     ms, flops = mb.probe("mfma", buf, 2000)
     assert 0 < flops / (ms * 1e-3) < 2.6e15
+    # data paths inside a compute unit: bytes per second over 256 compute units, far below anything absurd
+    # (an LDS port of 128 bytes per clock at 2.4 GHz is 79 TB/s over the chip; cached reads may exceed it)
+    for kind in ("lds_read", "lds_read_transposed", "copy_to_lds_async", "copy_via_registers"):
+        ms, nbytes = mb.probe(kind, buf, 200)
+        assert nbytes > 0 and 1e12 < nbytes / (ms * 1e-3) < 2.0e14, (kind, ms, nbytes)
 
 
 @pytest.mark.gpu
