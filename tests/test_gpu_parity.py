@@ -216,6 +216,14 @@ def test_random_shapes_campaign(campaign):
         run_case(lay, B, H, d, topk, dtype, s % 1000, causal=causal)
 
 
+def test_largest_chunk_count_the_list_builder_takes():
+    """C = 16384 chunks (the limit with k > 0: one list cursor per chunk in 64 KB of LDS), every token a
+    chunk of its own, 256 windows of 64 chunks; routing walks up to 512 score tiles per query."""
+    lay = mi.multishot_layout(1, 0, 256, 64, 1, "frame")
+    assert lay.C == 16384 and lay.N == 16384
+    run_case(lay, 1, 1, 64, 2, torch.bfloat16, seed=42)
+
+
 def test_long_chunks_take_the_tiled_routed_path():
     """Chunks of 520 keys do not fit the chunk-resident routed forward (<= 288 keys kept in LDS):
     the query-tile x key-tile routed kernel must give the same answer (sweep config's chunk 520)."""
