@@ -1,6 +1,7 @@
 """Host-side sanitizer builds (no GPU): the C oracle and the host half of the library's C ABI
 are compiled with -fsanitize=address,undefined and driven by the two small programs under
-tests/sanitize/. A report from either sanitizer fails the test. GPU code is not instrumented
+tests/sanitize/; a third program drives the host entry points from four threads under
+-fsanitize=thread. A report from any sanitizer fails the test. GPU code is not instrumented
 (device sanitizers are not available); the other translation units are linked as built."""
 import os
 import shutil
@@ -51,4 +52,25 @@ def test_abi_host_paths_under_address_and_undefined_sanitizers(tmp_path):
     _run(["hipcc", "--offload-arch=gfx950", *san, drv, obj, *others, "-o", exe])
     r = _run([exe], env=ENV)
     _clean(r)
+    assert r.stdout.startswith("ok ")
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None or not os.path.exists("/opt/rocm/llvm/bin/clang++"), reason="ROCm toolchain not found")
+def test_abi_host_paths_from_four_threads_under_thread_sanitizer(tmp_path):
+    """The library's host state (per-thread error string, profiling records and the list-tag registry behind
+    their mutexes) driven from four threads at once, host side built with -fsanitize=thread."""
+    from paper_2508_21058_amd import build as hb
+    hb.build()
+    san = ["-Xarch_host", "-fsanitize=thread"]
+    obj = str(tmp_path / "moc_api_tsan.o")
+    _run(["hipcc", "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fPIC", "-Xclang", "-target-feature",
+          "-Xclang", "-packed-fp32-ops", *san, "-c", os.path.join(hb.CSRC, "moc_api.hip"), "-o", obj])
+    others = [os.path.join(hb.OBJ, u + ".o") for u in hb.UNITS if u != "moc_api"]
+    exe, drv = str(tmp_path / "abi_tsan"), str(tmp_path / "abi_host_threads.o")
+    _run(["/opt/rocm/llvm/bin/clang++", "-O1", "-g", "-std=c++17", "-fsanitize=thread", "-c",
+          os.path.join(SAN, "abi_host_threads.cpp"), "-o", drv])
+    _run(["hipcc", "--offload-arch=gfx950", *san, drv, obj, *others, "-o", exe])
+    r = _run([exe], env=dict(ENV, TSAN_OPTIONS="halt_on_error=1"))
+    out = r.stdout + r.stderr
+    assert "ThreadSanitizer" not in out, out
     assert r.stdout.startswith("ok ")
