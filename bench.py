@@ -378,7 +378,10 @@ def measure(args, lay, cfg, tensors, steps, warmup, perturb, use_graph, with_pro
         roof = dict(kernel=dom, bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                     frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, avg_ms=kernels[dom]["ms"])
     if dom in traffic:
-        roof["traffic"] = {"hbm_GB_per_launch": traffic[dom], "source": tsrc}
+        # HBM bytes per launch of the dominant kernel (FETCH_SIZE + WRITE_SIZE counter runs, scaled; see the source file)
+        roof["traffic"] = round(traffic[dom] * 1e9)
+        roof["traffic_unit"] = "bytes per launch"
+        roof["traffic_source"] = tsrc
 
     measured = None
     if with_probes:
