@@ -18,10 +18,15 @@
  *     hipMalloc'ed memory owned by the caller; they must be 16-byte aligned.
  *   - Every call only enqueues work on `stream` (a hipStream_t, may be NULL for
  *     the default stream) and returns without synchronising, except
- *     moc_chunk_meta / moc_meta_copy_tables which also do small blocking copies.
+ *     moc_chunk_meta / moc_meta_copy_tables, which also do small blocking
+ *     copies, and the calls whose own comment says that they wait for their
+ *     work (moc_outer_route, moc_gather_rows, moc_route_fused_status,
+ *     moc_prof_read, moc_probe).
  *   - The library allocates device memory only inside moc_chunk_meta (a few
  *     small tables owned by the moc_meta handle). All other scratch space is a
- *     caller-owned workspace whose size the *_workspace_bytes calls report.
+ *     caller-owned workspace whose size the *_workspace_bytes calls report;
+ *     the one exception is moc_route_static, whose scratch is a static device
+ *     array of MOC_STATIC_SCRATCH_BYTES inside the library.
  *   - Return value: MOC_OK (0) or a negative moc_status. Nothing throws, aborts
  *     or prints. All argument checks happen before any device work.
  *     moc_last_error() returns a thread-local detail string of the last failure.
